@@ -1,0 +1,202 @@
+/*
+ * noloco.h - C ABI of the NoLoCo outer optimizer step for AMD MI355X (gfx950).
+ *
+ * Method: arxiv 2506.10911, section "Outer optimizer step with modified Nesterov
+ * momentum".  W worker replicas of one pipeline stage's parameters live stacked in one
+ * GPU's HBM; an outer step partitions the workers into random subgroups and applies,
+ * per subgroup G of size n and per parameter k,
+ *
+ *   Eq. 1   Delta_j  = phi_j - theta_j                       (j in G; outer weights minus
+ *                                                             local weights after the inner steps)
+ *   Eq. 2   delta'_i = alpha*delta_i - (beta/n)*sum_j Delta_j
+ *                      - gamma*(phi_i - (1/n)*sum_j phi_j)   (i in G, j over all of G, i included)
+ *   Eq. 3   phi'_i   = phi_i + delta'_i
+ *   restart theta'_i = phi'_i   (the next inner phase starts from the slow weights;
+ *                                rounded to nearest-even when theta is stored as bf16)
+ *
+ * in place, in IEEE binary32 with one rounding per operation (no fused multiply-add),
+ * sums taken in ascending worker order.
+ *
+ * Conventions for every entry point
+ *   - returns a noloco_status; never throws, never aborts, never prints;
+ *   - all pointers are borrowed: the caller owns every host array and every device
+ *     buffer; host arrays may be freed as soon as the call returns;
+ *   - "device" pointers are HIP device memory of the GPU that is current when the
+ *     launch plan is created; "host" pointers are ordinary process memory;
+ *   - GPU work is enqueued on the caller's stream and is NOT synchronised;
+ *   - the library keeps no global state; a launch plan is immutable after creation
+ *     (except through noloco_launch_plan_tune) and may be used from several threads.
+ */
+#ifndef NOLOCO_H_
+#define NOLOCO_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum noloco_status {
+  NOLOCO_OK = 0,
+  NOLOCO_ERR_NULL = 1,            /* a required pointer is null */
+  NOLOCO_ERR_INVALID_ARG = 2,     /* a size, dtype or layout field is out of range, or does not match the plan */
+  NOLOCO_ERR_BAD_GROUPING = 3,    /* groups are not a partition of a subset of the workers / W not divisible by n */
+  NOLOCO_ERR_SEGMENT_OVERLAP = 4, /* two segments share an element, or a segment leaves the row */
+  NOLOCO_ERR_ALIGNMENT = 5,       /* a base pointer or the worker stride is not aligned as required */
+  NOLOCO_ERR_DEVICE = 6,          /* the HIP runtime reported an error */
+  NOLOCO_ERR_UNSUPPORTED = 7      /* a documented limit is exceeded (e.g. a group larger than NOLOCO_MAX_GROUP) */
+} noloco_status;
+
+typedef enum noloco_dtype { NOLOCO_F32 = 0, NOLOCO_BF16 = 1 } noloco_dtype;
+
+/* Largest subgroup one call can handle (its member list travels in the kernel arguments). */
+#define NOLOCO_MAX_GROUP 256
+/* Required alignment of phi/delta/theta base addresses, in bytes, and of worker_stride, in elements. */
+#define NOLOCO_BASE_ALIGN_BYTES 256
+#define NOLOCO_STRIDE_ALIGN_ELEMS 64
+
+/*
+ * Subgroup sampling (section "Outer optimizer step ...": a random subgroup of n of the
+ * N instances, re-sampled every iteration; section "Inner optimizer step ...": groups
+ * come from random permutations).  Host only, integers only, a pure function of its
+ * arguments, so a resumed run replays the same groups.
+ *
+ * The permutation is a Fisher-Yates shuffle (index W-1 down to 1, partner drawn from
+ * [0, i]) driven by SplitMix64 started at mix64(seed ^ mix64(step + 0x9E3779B97F4A7C15)),
+ * with rejection of the lowest (2^64 mod m) draws for an unbiased partner; the shuffled
+ * list is cut into consecutive chunks of n and every chunk is sorted ascending.
+ *
+ *   seed, step     any 64-bit values (step = outer iteration counter t)
+ *   W              number of workers, >= 1
+ *   n              subgroup size, 1 <= n <= W, must divide W (else NOLOCO_ERR_BAD_GROUPING)
+ *   members        host, out, int32[W]: worker ids, group g is members[g*n .. g*n+n)
+ *   group_offsets  host, out, int32[W/n + 1]: group_offsets[g] = g*n
+ */
+noloco_status noloco_plan_groups(uint64_t seed, uint64_t step, int32_t W, int32_t n,
+                                 int32_t* members, int32_t* group_offsets);
+
+/* One tensor of the arena: `numel` consecutive elements starting `offset` elements into
+ * every worker's row. */
+typedef struct noloco_segment {
+  int64_t offset;
+  int64_t numel;
+} noloco_segment;
+
+/*
+ * The parameter arena: three device arrays of W rows, row w starting at
+ * base + w * worker_stride elements.  phi (slow / outer weights) and delta (outer
+ * momentum) are float; theta (fast / local weights) is float or bf16 (theta_dtype).
+ * Only elements inside a segment belong to the method; everything else in a row
+ * (gaps, padding up to worker_stride) is never read for its value and never written.
+ * Bases must be NOLOCO_BASE_ALIGN_BYTES-aligned and worker_stride a multiple of
+ * NOLOCO_STRIDE_ALIGN_ELEMS; segment offsets and lengths are arbitrary (odd is fine).
+ * Segments (host array) may come in any order, may leave gaps, must not overlap and
+ * must end at or before worker_stride; empty segments are ignored.
+ */
+typedef struct noloco_arena {
+  float* phi;              /* device, in/out */
+  float* delta;            /* device, in/out */
+  void* theta;             /* device, in/out, float or bf16 */
+  int64_t worker_stride;   /* elements between consecutive workers' rows, same for all three arrays */
+  int32_t W;               /* number of worker rows */
+  int32_t theta_dtype;     /* noloco_dtype */
+  const noloco_segment* segments; /* host, [num_segments] */
+  int32_t num_segments;
+} noloco_arena;
+
+/* Eq. 2's coefficients: alpha = outer momentum, beta = outer learning rate,
+ * gamma = pull towards the subgroup mean of the slow weights. */
+typedef struct noloco_hparams {
+  float alpha;
+  float beta;
+  float gamma;
+} noloco_hparams;
+
+/*
+ * Pure host helper behind the multi-tensor dispatch: validates a segment list against a
+ * row of `worker_stride` elements, sorts it and merges touching segments into maximal
+ * contiguous runs.
+ *   runs_out   host, out, capacity num_segments entries (may be null to only validate/count)
+ *   num_runs   host, out
+ * Errors: NOLOCO_ERR_SEGMENT_OVERLAP (overlap or out of row), NOLOCO_ERR_INVALID_ARG
+ * (negative offset/numel/count).
+ */
+noloco_status noloco_merge_segments(const noloco_segment* segments, int32_t num_segments,
+                                    int64_t worker_stride, noloco_segment* runs_out,
+                                    int32_t* num_runs);
+
+/*
+ * Multi-tensor launch table.  Validates the arena layout (W, worker_stride, theta_dtype,
+ * segments, alignment of the three base pointers), merges segments into runs, cuts runs
+ * into tiles and uploads the table to the current device (one small hipMalloc, freed by
+ * noloco_launch_plan_destroy).  The plan depends on the layout only: the same plan serves
+ * any three base pointers with the same layout.  Build once per arena, reuse every step.
+ * On error *out is null.
+ */
+typedef struct noloco_launch_plan noloco_launch_plan;
+noloco_status noloco_launch_plan_create(const noloco_arena* arena, noloco_launch_plan** out);
+noloco_status noloco_launch_plan_destroy(noloco_launch_plan* plan);
+
+/* Facts about a plan, for harnesses and tests.  Any out pointer may be null. */
+noloco_status noloco_launch_plan_info(const noloco_launch_plan* plan, int64_t* elements_per_worker,
+                                      int32_t* num_runs, int64_t* num_tiles, int32_t* tile_elems);
+
+/*
+ * Launch-shape knobs; the defaults are the measured best on MI355X.  Results never depend
+ * on them, only speed does.  A field set to -1 keeps its current value.
+ *   vectors_per_thread  16-byte vectors each thread handles per tile: 1, 2 or 4
+ *   nontemporal         1 = streaming (non-temporal) loads and stores, 0 = ordinary
+ *   group_major         1 = consecutive workgroups walk the tiles of one group,
+ *                       0 = consecutive workgroups take the same tile of successive groups
+ */
+typedef struct noloco_tuning {
+  int32_t vectors_per_thread;
+  int32_t nontemporal;
+  int32_t group_major;
+} noloco_tuning;
+noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan, const noloco_tuning* tuning);
+
+/*
+ * One outer step (Eq. 1-3 and the restart of the fast weights), fused, in place, enqueued
+ * on `hip_stream` (a hipStream_t; null = the default stream).  Returns after the launch.
+ *
+ *   plan           from noloco_launch_plan_create for this layout
+ *   arena          base pointers for this step; W, worker_stride and theta_dtype must match
+ *                  the plan (arena->segments is not read again)
+ *   hparams        alpha, beta, gamma of Eq. 2
+ *   members        host, int32[group_offsets[num_groups]]: worker ids, any order inside a group
+ *   group_offsets  host, int32[num_groups + 1], group_offsets[0] = 0, non-decreasing;
+ *                  group g is members[group_offsets[g] .. group_offsets[g+1])
+ *   num_groups     >= 0
+ *
+ * The groups must be disjoint and hold valid worker ids (NOLOCO_ERR_BAD_GROUPING
+ * otherwise, nothing is launched).  They need not cover all workers: rows of workers in
+ * no group are left untouched (a peer that dropped out of this round).  Groups may differ
+ * in size; each uses its own n in Eq. 2; a group of one has a zero third term; empty
+ * groups are ignored; a group larger than NOLOCO_MAX_GROUP gives NOLOCO_ERR_UNSUPPORTED.
+ * The result does not depend on the order of members inside a group nor on the order of
+ * the groups (sums run in ascending worker id), and is bit-identical from run to run.
+ * Subgroup sizes 1, 2, 4, 8 and 16 take register-resident kernels that move each byte
+ * once; other sizes take a two-pass kernel that reads phi twice.
+ */
+noloco_status noloco_outer_step(const noloco_launch_plan* plan, const noloco_arena* arena,
+                                const noloco_hparams* hparams, const int32_t* members,
+                                const int32_t* group_offsets, int32_t num_groups,
+                                void* hip_stream);
+
+/*
+ * Measurement aid, not part of the method: a plain device-to-device copy kernel of
+ * `bytes` bytes (a multiple of 16; both pointers 16-byte aligned) on `hip_stream`.
+ * Harnesses use it as the "achievable bandwidth" yardstick and to calibrate the
+ * profiler's HBM byte counters against a transfer of known size.
+ */
+noloco_status noloco_copy_probe(void* dst_device, const void* src_device, int64_t bytes,
+                                void* hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char* noloco_strerror(noloco_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NOLOCO_H_ */

@@ -1,0 +1,240 @@
+// C ABI of the NoLoCo outer step: argument checking, the launch plan, and the split of one
+// outer step into kernel launches.  All arithmetic of the method is in kernels.hip.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <map>
+#include <new>
+#include <vector>
+
+#include "noloco_internal.h"
+
+namespace {
+
+using noloco::Span;
+
+constexpr int32_t kTileSizes[3] = {1024, 2048, 4096};  // kBlockThreads * kVecElems * {1, 2, 4}
+
+bool aligned(const void* p, uintptr_t bytes) {
+  return (reinterpret_cast<uintptr_t>(p) % bytes) == 0;
+}
+
+}  // namespace
+
+struct noloco_launch_plan {
+  int device = -1;
+  int32_t W = 0;
+  int32_t theta_dtype = 0;
+  int64_t stride = 0;
+  int64_t elements = 0;                      // real elements per worker
+  std::vector<noloco_segment> runs;          // host copy, sorted and merged
+  Span* dev_spans = nullptr;                 // one allocation holding the three tables
+  int64_t table_offset[3] = {0, 0, 0};       // entry index of each table inside dev_spans
+  int64_t tiles[3] = {0, 0, 0};              // tiles per group for each tile size
+  noloco::KernelChoice choice{2, 1, 1};
+};
+
+extern "C" noloco_status noloco_launch_plan_create(const noloco_arena* arena,
+                                                   noloco_launch_plan** out) {
+  if (out == nullptr) return NOLOCO_ERR_NULL;
+  *out = nullptr;
+  if (arena == nullptr) return NOLOCO_ERR_NULL;
+  if (arena->phi == nullptr || arena->delta == nullptr || arena->theta == nullptr)
+    return NOLOCO_ERR_NULL;
+  if (arena->W < 1 || arena->worker_stride < 0 || arena->num_segments < 0)
+    return NOLOCO_ERR_INVALID_ARG;
+  if (arena->theta_dtype != NOLOCO_F32 && arena->theta_dtype != NOLOCO_BF16)
+    return NOLOCO_ERR_INVALID_ARG;
+  if (!aligned(arena->phi, NOLOCO_BASE_ALIGN_BYTES) || !aligned(arena->delta, NOLOCO_BASE_ALIGN_BYTES) ||
+      !aligned(arena->theta, NOLOCO_BASE_ALIGN_BYTES) ||
+      arena->worker_stride % NOLOCO_STRIDE_ALIGN_ELEMS != 0)
+    return NOLOCO_ERR_ALIGNMENT;
+
+  noloco_launch_plan* plan = new (std::nothrow) noloco_launch_plan;
+  if (plan == nullptr) return NOLOCO_ERR_DEVICE;
+  noloco_status st = noloco::merge_segments(arena->segments, arena->num_segments,
+                                            arena->worker_stride, &plan->runs);
+  if (st != NOLOCO_OK) {
+    delete plan;
+    return st;
+  }
+  plan->W = arena->W;
+  plan->theta_dtype = arena->theta_dtype;
+  plan->stride = arena->worker_stride;
+  for (const noloco_segment& r : plan->runs) plan->elements += r.numel;
+
+  std::vector<Span> all, one;
+  for (int t = 0; t < 3; ++t) {
+    plan->table_offset[t] = static_cast<int64_t>(all.size());
+    plan->tiles[t] = noloco::build_spans(plan->runs, kTileSizes[t], &one);
+    all.insert(all.end(), one.begin(), one.end());
+  }
+  if (hipGetDevice(&plan->device) != hipSuccess ||
+      hipMalloc(reinterpret_cast<void**>(&plan->dev_spans), all.size() * sizeof(Span)) != hipSuccess) {
+    delete plan;
+    return NOLOCO_ERR_DEVICE;
+  }
+  // Synchronous copy from pageable memory: the table is final when create returns.
+  if (hipMemcpy(plan->dev_spans, all.data(), all.size() * sizeof(Span), hipMemcpyHostToDevice) !=
+      hipSuccess) {
+    (void)hipFree(plan->dev_spans);
+    delete plan;
+    return NOLOCO_ERR_DEVICE;
+  }
+  *out = plan;
+  return NOLOCO_OK;
+}
+
+extern "C" noloco_status noloco_launch_plan_destroy(noloco_launch_plan* plan) {
+  if (plan == nullptr) return NOLOCO_OK;
+  noloco_status st = NOLOCO_OK;
+  if (plan->dev_spans != nullptr && hipFree(plan->dev_spans) != hipSuccess) st = NOLOCO_ERR_DEVICE;
+  delete plan;
+  return st;
+}
+
+extern "C" noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan,
+                                                 const noloco_tuning* tuning) {
+  if (plan == nullptr || tuning == nullptr) return NOLOCO_ERR_NULL;
+  noloco::KernelChoice c = plan->choice;
+  if (tuning->vectors_per_thread != -1) {
+    if (tuning->vectors_per_thread != 1 && tuning->vectors_per_thread != 2 &&
+        tuning->vectors_per_thread != 4)
+      return NOLOCO_ERR_INVALID_ARG;
+    c.vectors_per_thread = tuning->vectors_per_thread;
+  }
+  if (tuning->nontemporal != -1) {
+    if (tuning->nontemporal != 0 && tuning->nontemporal != 1) return NOLOCO_ERR_INVALID_ARG;
+    c.nontemporal = tuning->nontemporal;
+  }
+  if (tuning->group_major != -1) {
+    if (tuning->group_major != 0 && tuning->group_major != 1) return NOLOCO_ERR_INVALID_ARG;
+    c.group_major = tuning->group_major;
+  }
+  plan->choice = c;
+  return NOLOCO_OK;
+}
+
+extern "C" noloco_status noloco_launch_plan_info(const noloco_launch_plan* plan,
+                                                 int64_t* elements_per_worker, int32_t* num_runs,
+                                                 int64_t* num_tiles, int32_t* tile_elems) {
+  if (plan == nullptr) return NOLOCO_ERR_NULL;
+  const int32_t te = noloco::tile_elems_for(2, plan->choice.vectors_per_thread);
+  int t = 0;
+  while (kTileSizes[t] != te) ++t;
+  if (elements_per_worker) *elements_per_worker = plan->elements;
+  if (num_runs) *num_runs = static_cast<int32_t>(plan->runs.size());
+  if (num_tiles) *num_tiles = plan->tiles[t];
+  if (tile_elems) *tile_elems = te;
+  return NOLOCO_OK;
+}
+
+extern "C" noloco_status noloco_outer_step(const noloco_launch_plan* plan, const noloco_arena* arena,
+                                           const noloco_hparams* hparams, const int32_t* members,
+                                           const int32_t* group_offsets, int32_t num_groups,
+                                           void* hip_stream) {
+  if (plan == nullptr || arena == nullptr || hparams == nullptr) return NOLOCO_ERR_NULL;
+  if (arena->phi == nullptr || arena->delta == nullptr || arena->theta == nullptr)
+    return NOLOCO_ERR_NULL;
+  if (num_groups < 0) return NOLOCO_ERR_INVALID_ARG;
+  if (num_groups > 0 && (members == nullptr || group_offsets == nullptr)) return NOLOCO_ERR_NULL;
+  if (arena->W != plan->W || arena->worker_stride != plan->stride ||
+      arena->theta_dtype != plan->theta_dtype)
+    return NOLOCO_ERR_INVALID_ARG;
+  if (!aligned(arena->phi, NOLOCO_BASE_ALIGN_BYTES) || !aligned(arena->delta, NOLOCO_BASE_ALIGN_BYTES) ||
+      !aligned(arena->theta, NOLOCO_BASE_ALIGN_BYTES))
+    return NOLOCO_ERR_ALIGNMENT;
+
+  // Validate the grouping completely before anything is launched.
+  if (num_groups > 0 && group_offsets[0] != 0) return NOLOCO_ERR_BAD_GROUPING;
+  std::vector<uint8_t> seen(static_cast<size_t>(plan->W), 0);
+  std::map<int32_t, std::vector<int32_t>> by_size;  // group size -> concatenated sorted member lists
+  for (int32_t g = 0; g < num_groups; ++g) {
+    const int32_t lo = group_offsets[g], hi = group_offsets[g + 1];
+    if (hi < lo) return NOLOCO_ERR_BAD_GROUPING;
+    for (int32_t a = lo; a < hi; ++a) {
+      const int32_t w = members[a];
+      if (w < 0 || w >= plan->W || seen[static_cast<size_t>(w)]) return NOLOCO_ERR_BAD_GROUPING;
+      seen[static_cast<size_t>(w)] = 1;
+    }
+  }
+  for (int32_t g = 0; g < num_groups; ++g) {
+    const int32_t lo = group_offsets[g], hi = group_offsets[g + 1];
+    const int32_t n = hi - lo;
+    if (n == 0) continue;
+    if (n > NOLOCO_MAX_GROUP) return NOLOCO_ERR_UNSUPPORTED;
+    std::vector<int32_t>& list = by_size[n];
+    const size_t at = list.size();
+    list.insert(list.end(), members + lo, members + hi);
+    std::sort(list.begin() + static_cast<ptrdiff_t>(at), list.end());  // sums run in ascending worker id
+  }
+  if (plan->elements == 0 || by_size.empty()) return NOLOCO_OK;
+
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) return NOLOCO_ERR_DEVICE;
+  if (device != plan->device) return NOLOCO_ERR_INVALID_ARG;
+
+  noloco::StepArgs args;
+  std::memset(&args, 0, sizeof(args));
+  args.phi = arena->phi;
+  args.delta = arena->delta;
+  args.theta = arena->theta;
+  args.stride = plan->stride;
+  args.num_spans = static_cast<int32_t>(plan->runs.size());
+  args.alpha = hparams->alpha;
+  args.beta = hparams->beta;
+  args.gamma = hparams->gamma;
+  args.group_major = plan->choice.group_major;
+
+  for (const auto& kv : by_size) {
+    const int32_t n = kv.first;
+    const std::vector<int32_t>& list = kv.second;
+    const int32_t te = noloco::tile_elems_for(n, plan->choice.vectors_per_thread);
+    int t = 0;
+    while (kTileSizes[t] != te) ++t;
+    args.spans = plan->dev_spans + plan->table_offset[t];
+    args.num_tiles = plan->tiles[t];
+    args.n = n;
+    args.inv_n = 1.0f / static_cast<float>(n);
+    // Groups per launch: bounded by the member table in the kernel arguments and by the grid size.
+    const int64_t total_groups = static_cast<int64_t>(list.size()) / n;
+    int64_t per_launch = NOLOCO_MAX_GROUP / n;
+    const int64_t grid_limit = 0x7FFFFFFFll / std::max<int64_t>(args.num_tiles, 1);
+    if (grid_limit < 1) return NOLOCO_ERR_UNSUPPORTED;
+    per_launch = std::min(per_launch, grid_limit);
+    for (int64_t g0 = 0; g0 < total_groups; g0 += per_launch) {
+      const int64_t count = std::min(per_launch, total_groups - g0);
+      args.num_groups = static_cast<int32_t>(count);
+      std::memcpy(args.rows, list.data() + g0 * n, static_cast<size_t>(count * n) * sizeof(int32_t));
+      if (noloco::launch_outer_step(args, plan->theta_dtype, plan->choice, hip_stream) != 0)
+        return NOLOCO_ERR_DEVICE;
+    }
+  }
+  return NOLOCO_OK;
+}
+
+extern "C" noloco_status noloco_copy_probe(void* dst_device, const void* src_device, int64_t bytes,
+                                           void* hip_stream) {
+  if (dst_device == nullptr || src_device == nullptr) return NOLOCO_ERR_NULL;
+  if (bytes < 0 || bytes % 16 != 0) return NOLOCO_ERR_INVALID_ARG;
+  if (!aligned(dst_device, 16) || !aligned(src_device, 16)) return NOLOCO_ERR_ALIGNMENT;
+  if (bytes == 0) return NOLOCO_OK;
+  return noloco::launch_copy_probe(dst_device, src_device, bytes, hip_stream) == 0 ? NOLOCO_OK
+                                                                                   : NOLOCO_ERR_DEVICE;
+}
+
+extern "C" const char* noloco_strerror(noloco_status status) {
+  switch (status) {
+    case NOLOCO_OK: return "ok";
+    case NOLOCO_ERR_NULL: return "a required pointer is null";
+    case NOLOCO_ERR_INVALID_ARG: return "invalid argument";
+    case NOLOCO_ERR_BAD_GROUPING: return "groups are not a valid partition";
+    case NOLOCO_ERR_SEGMENT_OVERLAP: return "segments overlap or leave the row";
+    case NOLOCO_ERR_ALIGNMENT: return "base pointer or worker stride misaligned";
+    case NOLOCO_ERR_DEVICE: return "HIP runtime error";
+    case NOLOCO_ERR_UNSUPPORTED: return "documented limit exceeded";
+  }
+  return "unknown status";
+}

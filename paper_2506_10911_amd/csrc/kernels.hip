@@ -1,0 +1,374 @@
+// Fused NoLoCo outer step for gfx950 (arxiv 2506.10911, section "Outer optimizer step with
+// modified Nesterov momentum", Eq. 1-3, plus the restart of the fast weights).
+//
+// The operation is a pure stream: per worker-parameter it reads phi, delta, theta once and
+// writes them once, with about ten flops in between, so HBM bandwidth is the only roofline
+// that matters.  The kernels are therefore organised around memory access:
+//   * one thread owns one 16-byte vector of four consecutive columns of ONE subgroup and
+//     does the whole step for all n members of it, so every byte is moved exactly once and
+//     the subgroup reduction never leaves registers;
+//   * a wave's load instruction covers 1 KiB of consecutive addresses of one row
+//     (global_load_dwordx4; 8 bytes per lane for bf16 theta);
+//   * all 3*n*U loads of a thread are issued before the first use, to keep enough bytes in
+//     flight per CU to cover HBM latency;
+//   * a workgroup is one tile (1024*U columns) of one subgroup; tiles whose column range
+//     is whole take a branch-free path, the first/last tile of a run takes a path that
+//     handles partially owned vectors element by element.
+//
+// Arithmetic contract (binary32, one rounding per operation, no contraction; this file is
+// compiled with -ffp-contract=off), members a = 0..n-1 in ascending worker id:
+//   D_a = phi_a - widen(theta_a);  SD = D_0 (+ D_a ...);  SP = phi_0 (+ phi_a ...)
+//   mD = SD * inv_n;  mP = SP * inv_n
+//   delta'_a = (alpha*delta_a - beta*mD) - gamma*(phi_a - mP)
+//   phi'_a = phi_a + delta'_a;  theta'_a = narrow(phi'_a)
+#include <hip/hip_runtime.h>
+
+#include "noloco_internal.h"
+
+namespace noloco {
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned short h4 __attribute__((ext_vector_type(4)));  // four bf16 bit patterns
+typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+
+struct Bf16Tag {};  // theta stored as bf16; `float` doubles as the tag for fp32 theta
+
+// bf16 is the upper half of binary32.  Narrowing rounds to nearest, ties to even, by adding
+// 0x7FFF plus the lowest kept bit and dropping 16 bits; NaN is kept as a quiet NaN.
+__device__ __forceinline__ unsigned int narrow_bits(unsigned int u) {
+  const unsigned int r = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  const unsigned int q = (u >> 16) | 0x0040u;
+  return ((u & 0x7FFFFFFFu) > 0x7F800000u) ? q : r;
+}
+
+// How `theta` is held in memory for a lane that works on V (f4 = four columns, float = one).
+template <typename Tag, typename V> struct ThetaMem;
+template <> struct ThetaMem<float, f4> {
+  typedef float elem; typedef f4 mem;
+  static __device__ __forceinline__ f4 widen(f4 m) { return m; }
+  static __device__ __forceinline__ f4 narrow(f4 v) { return v; }
+};
+template <> struct ThetaMem<float, float> {
+  typedef float elem; typedef float mem;
+  static __device__ __forceinline__ float widen(float m) { return m; }
+  static __device__ __forceinline__ float narrow(float v) { return v; }
+};
+template <> struct ThetaMem<Bf16Tag, f4> {
+  typedef unsigned short elem; typedef h4 mem;
+  static __device__ __forceinline__ f4 widen(h4 m) {
+    u4 w = __builtin_convertvector(m, u4) << 16;
+    return __builtin_bit_cast(f4, w);
+  }
+  static __device__ __forceinline__ h4 narrow(f4 v) {
+    u4 u = __builtin_bit_cast(u4, v);
+    u4 r;
+    r.x = narrow_bits(u.x); r.y = narrow_bits(u.y); r.z = narrow_bits(u.z); r.w = narrow_bits(u.w);
+    return __builtin_convertvector(r, h4);
+  }
+};
+template <> struct ThetaMem<Bf16Tag, float> {
+  typedef unsigned short elem; typedef unsigned short mem;
+  static __device__ __forceinline__ float widen(unsigned short m) {
+    return __uint_as_float(static_cast<unsigned int>(m) << 16);
+  }
+  static __device__ __forceinline__ unsigned short narrow(float v) {
+    return static_cast<unsigned short>(narrow_bits(__float_as_uint(v)));
+  }
+};
+
+template <bool NT, typename T> __device__ __forceinline__ T ld(const T* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT, typename T> __device__ __forceinline__ void st(T* p, T v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+// Which tile of which group this workgroup owns, and that tile's column range.
+struct TileRef {
+  uint32_t group;
+  int64_t base;   // first column of the tile's aligned block
+  int64_t c0;     // owned columns are [c0, c1)
+  int64_t c1;
+};
+
+__device__ __forceinline__ TileRef locate_tile(const StepArgs& a, int tile_elems) {
+  const uint32_t tiles = static_cast<uint32_t>(a.num_tiles);   // host guarantees tiles*groups < 2^31
+  const uint32_t wg = blockIdx.x;
+  uint32_t tile;
+  TileRef r;
+  if (a.group_major) {
+    r.group = wg / tiles;
+    tile = wg - r.group * tiles;
+  } else {
+    const uint32_t groups = static_cast<uint32_t>(a.num_groups);
+    tile = wg / groups;
+    r.group = wg - tile * groups;
+  }
+  int lo = 0, hi = a.num_spans;             // spans[hi] is the sentinel: its prefix is the tile total
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.spans[mid].tile_prefix <= static_cast<int64_t>(tile)) lo = mid; else hi = mid;
+  }
+  const Span s = a.spans[lo];
+  r.base = (s.first_block + (static_cast<int64_t>(tile) - s.tile_prefix)) * tile_elems;
+  r.c0 = r.base > s.col_begin ? r.base : s.col_begin;
+  const int64_t end = r.base + tile_elems;
+  r.c1 = end < s.col_end ? end : s.col_end;
+  return r;
+}
+
+// Eq. 1-3 and the restart for N members held in registers.  V is f4 or float.
+template <int N, typename Tag, typename V>
+__device__ __forceinline__ void update_members(V (&p)[N], V (&d)[N],
+                                               typename ThetaMem<Tag, V>::mem (&t)[N],
+                                               float alpha, float beta, float gamma, float inv_n) {
+  typedef ThetaMem<Tag, V> TM;
+  V sum_D = p[0] - TM::widen(t[0]);          // Eq. 1, and the two sums of Eq. 2
+  V sum_P = p[0];
+#pragma unroll
+  for (int j = 1; j < N; ++j) {
+    const V D = p[j] - TM::widen(t[j]);
+    sum_D = sum_D + D;
+    sum_P = sum_P + p[j];
+  }
+  const V mean_P = sum_P * inv_n;
+  const V t2 = beta * (sum_D * inv_n);
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    const V t1 = alpha * d[j];
+    const V t3 = gamma * (p[j] - mean_P);
+    const V d_new = (t1 - t2) - t3;          // Eq. 2
+    const V p_new = p[j] + d_new;            // Eq. 3
+    d[j] = d_new;
+    p[j] = p_new;
+    t[j] = TM::narrow(p_new);                // restart of the fast weights
+  }
+}
+
+// One lane's whole step at column `c` for a compile-time group size: load all, update, store all.
+template <int N, typename Tag, typename V, bool NT>
+__device__ __forceinline__ void step_at(float* const (&P)[N], float* const (&D)[N],
+                                        typename ThetaMem<Tag, V>::elem* const (&T)[N], int64_t c,
+                                        const StepArgs& a) {
+  typedef ThetaMem<Tag, V> TM;
+  typedef typename TM::mem TMem;
+  V p[N], d[N];
+  TMem t[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    p[j] = ld<NT>(reinterpret_cast<const V*>(P[j] + c));
+    t[j] = ld<NT>(reinterpret_cast<const TMem*>(T[j] + c));
+    d[j] = ld<NT>(reinterpret_cast<const V*>(D[j] + c));
+  }
+  update_members<N, Tag, V>(p, d, t, a.alpha, a.beta, a.gamma, a.inv_n);
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    st<NT>(reinterpret_cast<V*>(P[j] + c), p[j]);
+    st<NT>(reinterpret_cast<V*>(D[j] + c), d[j]);
+    st<NT>(reinterpret_cast<TMem*>(T[j] + c), t[j]);
+  }
+}
+
+// Register-resident kernel: group size N known at compile time, U vectors per thread.
+template <int N, typename Tag, int U, bool NT>
+__global__ void __launch_bounds__(kBlockThreads) outer_step_fixed(const StepArgs a) {
+  constexpr int kTile = kBlockThreads * kVecElems * U;
+  typedef ThetaMem<Tag, f4> TM;
+  typedef typename TM::elem TElem;
+  typedef typename TM::mem TMem;
+
+  const TileRef tr = locate_tile(a, kTile);
+  float* P[N];
+  float* D[N];
+  TElem* T[N];
+#pragma unroll
+  for (int j = 0; j < N; ++j) {
+    const int64_t off = static_cast<int64_t>(a.rows[tr.group * N + j]) * a.stride;
+    P[j] = a.phi + off;
+    D[j] = a.delta + off;
+    T[j] = static_cast<TElem*>(a.theta) + off;
+  }
+  const int64_t lane_col = tr.base + static_cast<int64_t>(threadIdx.x) * kVecElems;
+
+  if (tr.c0 == tr.base && tr.c1 == tr.base + kTile) {
+    // Whole tile: every vector is owned entirely.  Loads first, all of them.
+    f4 p[U][N], d[U][N];
+    TMem t[U][N];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t c = lane_col + u * (kBlockThreads * kVecElems);
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        p[u][j] = ld<NT>(reinterpret_cast<const f4*>(P[j] + c));
+        t[u][j] = ld<NT>(reinterpret_cast<const TMem*>(T[j] + c));
+        d[u][j] = ld<NT>(reinterpret_cast<const f4*>(D[j] + c));
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      update_members<N, Tag, f4>(p[u], d[u], t[u], a.alpha, a.beta, a.gamma, a.inv_n);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t c = lane_col + u * (kBlockThreads * kVecElems);
+#pragma unroll
+      for (int j = 0; j < N; ++j) {
+        st<NT>(reinterpret_cast<f4*>(P[j] + c), p[u][j]);
+        st<NT>(reinterpret_cast<f4*>(D[j] + c), d[u][j]);
+        st<NT>(reinterpret_cast<TMem*>(T[j] + c), t[u][j]);
+      }
+    }
+    return;
+  }
+
+  // First or last tile of a run: a vector may be owned whole, in part, or not at all.
+  float* const (&Pc)[N] = P;
+  float* const (&Dc)[N] = D;
+  TElem* const (&Tc)[N] = T;
+  for (int u = 0; u < U; ++u) {
+    const int64_t c = lane_col + u * (kBlockThreads * kVecElems);
+    if (c >= tr.c0 && c + kVecElems <= tr.c1) {
+      step_at<N, Tag, f4, NT>(Pc, Dc, Tc, c, a);
+    } else {
+      for (int e = 0; e < kVecElems; ++e)
+        if (c + e >= tr.c0 && c + e < tr.c1) step_at<N, Tag, float, false>(Pc, Dc, Tc, c + e, a);
+    }
+  }
+}
+
+// Two passes over the members for a group size only known at run time: the first forms the
+// two sums, the second re-reads phi, reads delta and writes.  V is f4 or float.
+template <typename Tag, typename V, bool NT>
+__device__ __forceinline__ void two_pass_at(const StepArgs& a, const int32_t* rows, int64_t c) {
+  typedef ThetaMem<Tag, V> TM;
+  typedef typename TM::elem TElem;
+  typedef typename TM::mem TMem;
+  const int n = a.n;
+  TElem* const theta = static_cast<TElem*>(a.theta);
+  int64_t at = static_cast<int64_t>(rows[0]) * a.stride + c;
+  V sum_P = *reinterpret_cast<const V*>(a.phi + at);
+  V sum_D = sum_P - TM::widen(ld<NT>(reinterpret_cast<const TMem*>(theta + at)));
+  for (int j = 1; j < n; ++j) {
+    at = static_cast<int64_t>(rows[j]) * a.stride + c;
+    const V p = *reinterpret_cast<const V*>(a.phi + at);        // ordinary load: read again below
+    const V D = p - TM::widen(ld<NT>(reinterpret_cast<const TMem*>(theta + at)));
+    sum_D = sum_D + D;
+    sum_P = sum_P + p;
+  }
+  const V mean_P = sum_P * a.inv_n;
+  const V t2 = a.beta * (sum_D * a.inv_n);
+  for (int j = 0; j < n; ++j) {
+    at = static_cast<int64_t>(rows[j]) * a.stride + c;
+    const V p = ld<NT>(reinterpret_cast<const V*>(a.phi + at));
+    const V d = ld<NT>(reinterpret_cast<const V*>(a.delta + at));
+    const V t1 = a.alpha * d;
+    const V t3 = a.gamma * (p - mean_P);
+    const V d_new = (t1 - t2) - t3;
+    const V p_new = p + d_new;
+    st<NT>(reinterpret_cast<V*>(a.delta + at), d_new);
+    st<NT>(reinterpret_cast<V*>(a.phi + at), p_new);
+    st<NT>(reinterpret_cast<TMem*>(theta + at), TM::narrow(p_new));
+  }
+}
+
+template <typename Tag, bool NT>
+__global__ void __launch_bounds__(kBlockThreads) outer_step_generic(const StepArgs a) {
+  constexpr int kTile = kBlockThreads * kVecElems;
+  const TileRef tr = locate_tile(a, kTile);
+  const int32_t* rows = a.rows + tr.group * a.n;
+  const int64_t c = tr.base + static_cast<int64_t>(threadIdx.x) * kVecElems;
+  if (c >= tr.c0 && c + kVecElems <= tr.c1) {
+    two_pass_at<Tag, f4, NT>(a, rows, c);
+  } else {
+    for (int e = 0; e < kVecElems; ++e)
+      if (c + e >= tr.c0 && c + e < tr.c1) two_pass_at<Tag, float, false>(a, rows, c + e);
+  }
+}
+
+// Plain streaming copy: 4 vectors per thread, loads before stores.
+__global__ void __launch_bounds__(kBlockThreads) copy_probe_kernel(f4* __restrict__ dst,
+                                                                   const f4* __restrict__ src,
+                                                                   int64_t vectors) {
+  const int64_t first = static_cast<int64_t>(blockIdx.x) * (kBlockThreads * 4) + threadIdx.x;
+  f4 v[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = first + u * kBlockThreads;
+    if (i < vectors) v[u] = __builtin_nontemporal_load(src + i);
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = first + u * kBlockThreads;
+    if (i < vectors) __builtin_nontemporal_store(v[u], dst + i);
+  }
+}
+
+template <int N, typename Tag, int U>
+hipError_t launch_fixed_nt(const StepArgs& args, bool nt, dim3 grid, hipStream_t s) {
+  if (nt) hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, true>), grid, dim3(kBlockThreads), 0, s, args);
+  else    hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, false>), grid, dim3(kBlockThreads), 0, s, args);
+  return hipGetLastError();
+}
+
+template <int N, typename Tag>
+hipError_t launch_fixed(const StepArgs& args, int u, bool nt, dim3 grid, hipStream_t s) {
+  constexpr int kMaxU = N <= 2 ? 4 : (N == 4 ? 2 : 1);
+  if constexpr (kMaxU >= 4) if (u == 4) return launch_fixed_nt<N, Tag, 4>(args, nt, grid, s);
+  if constexpr (kMaxU >= 2) if (u == 2) return launch_fixed_nt<N, Tag, 2>(args, nt, grid, s);
+  return launch_fixed_nt<N, Tag, 1>(args, nt, grid, s);
+}
+
+template <typename Tag>
+hipError_t launch_for_dtype(const StepArgs& args, const KernelChoice& choice, hipStream_t s) {
+  const bool nt = choice.nontemporal != 0;
+  const int u = tile_elems_for(args.n, choice.vectors_per_thread) / (kBlockThreads * kVecElems);
+  const dim3 grid(static_cast<uint32_t>(args.num_tiles * args.num_groups));
+  switch (args.n) {
+    case 1: return launch_fixed<1, Tag>(args, u, nt, grid, s);
+    case 2: return launch_fixed<2, Tag>(args, u, nt, grid, s);
+    case 4: return launch_fixed<4, Tag>(args, u, nt, grid, s);
+    case 8: return launch_fixed<8, Tag>(args, u, nt, grid, s);
+    case 16: return launch_fixed<16, Tag>(args, u, nt, grid, s);
+    default: break;
+  }
+  if (nt) hipLaunchKernelGGL((outer_step_generic<Tag, true>), grid, dim3(kBlockThreads), 0, s, args);
+  else    hipLaunchKernelGGL((outer_step_generic<Tag, false>), grid, dim3(kBlockThreads), 0, s, args);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool has_fixed_kernel(int32_t n) { return n == 1 || n == 2 || n == 4 || n == 8 || n == 16; }
+
+int32_t tile_elems_for(int32_t n, int32_t vectors_per_thread) {
+  int32_t u = 1;
+  if (has_fixed_kernel(n)) {
+    const int32_t max_u = n <= 2 ? 4 : (n == 4 ? 2 : 1);
+    u = vectors_per_thread < max_u ? vectors_per_thread : max_u;
+  }
+  return kBlockThreads * kVecElems * u;
+}
+
+int launch_outer_step(const StepArgs& args, int32_t theta_dtype, const KernelChoice& choice,
+                      void* stream) {
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (args.num_tiles <= 0 || args.num_groups <= 0) return 0;
+  const hipError_t e = theta_dtype == NOLOCO_BF16 ? launch_for_dtype<Bf16Tag>(args, choice, s)
+                                                  : launch_for_dtype<float>(args, choice, s);
+  return static_cast<int>(e);
+}
+
+int launch_copy_probe(void* dst, const void* src, int64_t bytes, void* stream) {
+  const int64_t vectors = bytes / 16;
+  const int64_t per_block = kBlockThreads * 4;
+  const int64_t blocks = (vectors + per_block - 1) / per_block;
+  if (blocks > 0x7FFFFFFFll) return static_cast<int>(hipErrorInvalidValue);
+  hipLaunchKernelGGL(copy_probe_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kBlockThreads), 0,
+                     static_cast<hipStream_t>(stream), static_cast<f4*>(dst),
+                     static_cast<const f4*>(src), vectors);
+  return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace noloco

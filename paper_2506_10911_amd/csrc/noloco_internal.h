@@ -1,0 +1,63 @@
+// Types shared by the host side of the library and its kernels (not part of the C ABI).
+#pragma once
+
+#include <cstdint>
+#include <vector>
+
+#include "noloco.h"
+
+namespace noloco {
+
+constexpr int kBlockThreads = 256;   // four wave64 per workgroup
+constexpr int kVecElems = 4;         // one 16-byte fp32 vector per lane and load
+
+// A maximal contiguous run of arena elements, cut into tiles of `tile_elems` columns whose
+// boundaries sit at multiples of tile_elems in row coordinates.  The run's first and last
+// tile may be partial; all others are whole.
+struct Span {
+  int64_t col_begin;     // first element of the run (inclusive)
+  int64_t col_end;       // one past its last element
+  int64_t first_block;   // col_begin / tile_elems
+  int64_t tile_prefix;   // number of tiles in all earlier spans
+};
+
+// Kernel arguments of one launch: all groups in it have the same size n.
+struct StepArgs {
+  float* phi;
+  float* delta;
+  void* theta;
+  int64_t stride;          // elements between rows
+  const Span* spans;       // device, num_spans + 1 entries (last is a sentinel holding the tile total)
+  int32_t num_spans;
+  int32_t num_groups;      // groups in this launch
+  int64_t num_tiles;       // tiles per group
+  float alpha, beta, gamma, inv_n;
+  int32_t n;               // group size
+  int32_t group_major;     // workgroup -> (tile, group) order
+  int32_t rows[NOLOCO_MAX_GROUP];  // group g = rows[g*n .. g*n+n), ascending worker ids
+};
+
+struct KernelChoice {
+  int32_t vectors_per_thread;
+  int32_t nontemporal;
+  int32_t group_major;
+};
+
+// host: segment table -> runs (sorted, merged); see noloco_merge_segments
+noloco_status merge_segments(const noloco_segment* segments, int32_t num_segments,
+                             int64_t worker_stride, std::vector<noloco_segment>* runs);
+
+// host: runs -> spans for a tile size; returns the tile total
+int64_t build_spans(const std::vector<noloco_segment>& runs, int32_t tile_elems,
+                    std::vector<Span>* spans);
+
+// kernels.hip: enqueue one launch.  Returns hipError_t as int.
+int launch_outer_step(const StepArgs& args, int32_t theta_dtype, const KernelChoice& choice,
+                      void* stream);
+int launch_copy_probe(void* dst, const void* src, int64_t bytes, void* stream);
+
+// tile size in elements for a kernel choice and group size
+int32_t tile_elems_for(int32_t n, int32_t vectors_per_thread);
+bool has_fixed_kernel(int32_t n);
+
+}  // namespace noloco

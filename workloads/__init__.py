@@ -171,27 +171,30 @@ def fake_inner_phase_cpu(phi: np.ndarray, seed: int, step: int, sigma: float, th
 # Values, device side (torch; fills arenas too large to build on the host)
 # ---------------------------------------------------------------------------
 
-def fill_phi0_device(phi, P: int, seed: int, std: float = 0.02, chunk: int = 1 << 27):
-    """phi: torch float32 [W, stride] on the GPU. Row 0 gets N(0, std^2), the other rows copy it."""
+def fill_phi0_device(phi, seed: int, std: float = 0.02, chunk: int = 1 << 27):
+    """phi: torch float32 [W, stride] on the GPU. Row 0 gets N(0, std^2) over the whole row (gaps and
+    padding included; they belong to nobody), the other rows copy it: the common start phi_0."""
     import torch
     g = torch.Generator(device=phi.device)
     g.manual_seed(seed * (1 << 32) + 0x7068)
-    for a in range(0, P, chunk):
-        b = min(a + chunk, P)
+    stride = phi.shape[1]
+    for a in range(0, stride, chunk):
+        b = min(a + chunk, stride)
         phi[0, a:b].normal_(0.0, std, generator=g)
     for w in range(1, phi.shape[0]):
         phi[w].copy_(phi[0])
 
 
-def fake_inner_phase_device(theta, phi, P: int, seed: int, step: int, sigma: float, chunk: int = 1 << 27):
-    """theta[w, :P] = cast(phi[w, :P] + sigma z) in place, chunked so the temporaries stay small."""
+def fake_inner_phase_device(theta, phi, seed: int, step: int, sigma: float, chunk: int = 1 << 27):
+    """theta[w] = cast(phi[w] + sigma z) over whole rows, chunked so the temporaries stay small."""
     import torch
     g = torch.Generator(device=phi.device)
     g.manual_seed(seed * (1 << 32) + 0x6472 + step * 7919)
-    buf = torch.empty(min(chunk, P), dtype=torch.float32, device=phi.device)
+    stride = phi.shape[1]
+    buf = torch.empty(min(chunk, stride), dtype=torch.float32, device=phi.device)
     for w in range(phi.shape[0]):
-        for a in range(0, P, chunk):
-            b = min(a + chunk, P)
+        for a in range(0, stride, chunk):
+            b = min(a + chunk, stride)
             z = buf[: b - a]
             z.normal_(0.0, sigma, generator=g)
             z.add_(phi[w, a:b])
