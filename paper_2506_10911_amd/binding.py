@@ -47,6 +47,12 @@ def _load():
         raise ImportError(
             f"{_LIB_PATH} is missing: build it with `python -m paper_2506_10911_amd.build` "
             "(there is no fallback path)")
+    # The caller's device buffers come from PyTorch, so the library must bind to the HIP runtime
+    # PyTorch has loaded, not to a second copy: import torch first, then the loader reuses it.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(_LIB_PATH)
     L.noloco_plan_groups.restype = C.c_int
     L.noloco_plan_groups.argtypes = [C.c_uint64, C.c_uint64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
