@@ -146,13 +146,18 @@ noloco_status noloco_launch_plan_info(const noloco_launch_plan* plan, int64_t* e
  * on them, only speed does.  A field set to -1 keeps its current value.
  *   vectors_per_thread  16-byte vectors each thread handles per tile: 1, 2 or 4
  *   nontemporal         1 = streaming (non-temporal) loads and stores, 0 = ordinary
- *   group_major         1 = consecutive workgroups walk the tiles of one group,
- *                       0 = consecutive workgroups take the same tile of successive groups
+ *   group_major         1 = consecutive work items walk the tiles of one group,
+ *                       0 = consecutive work items take the same tile of successive groups
+ *   xcd_map             how workgroups (dealt round-robin to the 8 XCDs by the hardware) pick
+ *                       work items: 0 = workgroup i takes item i; 1 = each XCD takes one
+ *                       contiguous eighth of the items; c in [2, 4096] = each XCD takes runs
+ *                       of c consecutive items
  */
 typedef struct noloco_tuning {
   int32_t vectors_per_thread;
   int32_t nontemporal;
   int32_t group_major;
+  int32_t xcd_map;
 } noloco_tuning;
 noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan, const noloco_tuning* tuning);
 

@@ -39,7 +39,7 @@ class _HParams(C.Structure):
 
 class _Tuning(C.Structure):
     _fields_ = [("vectors_per_thread", C.c_int32), ("nontemporal", C.c_int32),
-                ("group_major", C.c_int32)]
+                ("group_major", C.c_int32), ("xcd_map", C.c_int32)]
 
 
 def _load():
@@ -161,8 +161,8 @@ class LaunchPlan:
         return {"elements_per_worker": e.value, "num_runs": r.value, "num_tiles": t.value,
                 "tile_elems": te.value}
 
-    def tune(self, vectors_per_thread=-1, nontemporal=-1, group_major=-1):
-        t = _Tuning(int(vectors_per_thread), int(nontemporal), int(group_major))
+    def tune(self, vectors_per_thread=-1, nontemporal=-1, group_major=-1, xcd_map=-1):
+        t = _Tuning(int(vectors_per_thread), int(nontemporal), int(group_major), int(xcd_map))
         _check(_lib.noloco_launch_plan_tune(self._handle, C.byref(t)), "noloco_launch_plan_tune")
 
     def destroy(self):

@@ -33,7 +33,7 @@ struct noloco_launch_plan {
   Span* dev_spans = nullptr;                 // one allocation holding the three tables
   int64_t table_offset[3] = {0, 0, 0};       // entry index of each table inside dev_spans
   int64_t tiles[3] = {0, 0, 0};              // tiles per group for each tile size
-  noloco::KernelChoice choice{2, 1, 1};
+  noloco::KernelChoice choice{2, 1, 1, 1};
 };
 
 extern "C" noloco_status noloco_launch_plan_create(const noloco_arena* arena,
@@ -113,6 +113,10 @@ extern "C" noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan,
     if (tuning->group_major != 0 && tuning->group_major != 1) return NOLOCO_ERR_INVALID_ARG;
     c.group_major = tuning->group_major;
   }
+  if (tuning->xcd_map != -1) {
+    if (tuning->xcd_map < 0 || tuning->xcd_map > 4096) return NOLOCO_ERR_INVALID_ARG;
+    c.xcd_map = tuning->xcd_map;
+  }
   plan->choice = c;
   return NOLOCO_OK;
 }
@@ -187,6 +191,7 @@ extern "C" noloco_status noloco_outer_step(const noloco_launch_plan* plan, const
   args.beta = hparams->beta;
   args.gamma = hparams->gamma;
   args.group_major = plan->choice.group_major;
+  args.xcd_map = plan->choice.xcd_map;
 
   for (const auto& kv : by_size) {
     const int32_t n = kv.first;
@@ -201,12 +206,14 @@ extern "C" noloco_status noloco_outer_step(const noloco_launch_plan* plan, const
     // Groups per launch: bounded by the member table in the kernel arguments and by the grid size.
     const int64_t total_groups = static_cast<int64_t>(list.size()) / n;
     int64_t per_launch = NOLOCO_MAX_GROUP / n;
-    const int64_t grid_limit = 0x7FFFFFFFll / std::max<int64_t>(args.num_tiles, 1);
+    // keep tiles * groups (plus the rounding the XCD map adds) inside a 31-bit grid
+    const int64_t grid_limit = 0x7FFF0000ll / std::max<int64_t>(args.num_tiles, 1);
     if (grid_limit < 1) return NOLOCO_ERR_UNSUPPORTED;
     per_launch = std::min(per_launch, grid_limit);
     for (int64_t g0 = 0; g0 < total_groups; g0 += per_launch) {
       const int64_t count = std::min(per_launch, total_groups - g0);
       args.num_groups = static_cast<int32_t>(count);
+      args.work_items = static_cast<uint32_t>(args.num_tiles * count);
       std::memcpy(args.rows, list.data() + g0 * n, static_cast<size_t>(count * n) * sizeof(int32_t));
       if (noloco::launch_outer_step(args, plan->theta_dtype, plan->choice, hip_stream) != 0)
         return NOLOCO_ERR_DEVICE;

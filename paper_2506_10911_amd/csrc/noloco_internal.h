@@ -33,7 +33,9 @@ struct StepArgs {
   int64_t num_tiles;       // tiles per group
   float alpha, beta, gamma, inv_n;
   int32_t n;               // group size
-  int32_t group_major;     // workgroup -> (tile, group) order
+  int32_t group_major;     // work item -> (tile, group) order
+  int32_t xcd_map;         // workgroup -> work item permutation, see noloco_tuning
+  uint32_t work_items;     // num_tiles * num_groups
   int32_t rows[NOLOCO_MAX_GROUP];  // group g = rows[g*n .. g*n+n), ascending worker ids
 };
 
@@ -41,7 +43,10 @@ struct KernelChoice {
   int32_t vectors_per_thread;
   int32_t nontemporal;
   int32_t group_major;
+  int32_t xcd_map;
 };
+
+constexpr uint32_t kXcds = 8;        // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
 
 // host: segment table -> runs (sorted, merged); see noloco_merge_segments
 noloco_status merge_segments(const noloco_segment* segments, int32_t num_segments,

@@ -1,0 +1,107 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+Columns of the arena are independent, so the oracle runs on a sample of columns (the first and
+last 64 elements of every tensor plus a strided sweep, all W rows) and is exact for those. The
+oracle keeps its own phi/delta across steps; before every step its fast weights for the sampled
+columns (drawn on the CPU from its own state) are written into the device arena, so both sides
+see bit-identical inputs there, while the rest of the arena gets device-drawn drift of the same
+distribution. Gaps of the gapped layout carry NaN canaries.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from harness import assert_state_equal, theta_to_device, to_bits
+
+pytestmark = pytest.mark.gpu
+
+nl = pytest.importorskip("paper_2506_10911_amd", reason="libnoloco.so not built")
+
+CASES = [
+    # name, steps compared, strided sample size
+    ("tiny", 10, 1 << 20),          # the whole arena
+    ("gpt125m", 6, 1 << 18),
+    ("stage1p3b", 4, 1 << 18),
+    ("stage6p8b", 3, 1 << 18),
+    ("ragged_tight", 6, 1 << 16),   # n cycles 2, 4, 8
+    ("ragged_gapped", 6, 1 << 16),
+]
+
+
+def gap_columns(wl):
+    inside = np.zeros(wl.stride, dtype=bool)
+    for o, n in wl.segments:
+        inside[o:o + n] = True
+    return np.flatnonzero(~inside)
+
+
+@pytest.mark.parametrize("name,steps,strided", CASES, ids=[c[0] for c in CASES])
+def test_full_size_sampled_parity(name, steps, strided):
+    wl = workloads.make(name)
+    W, S = wl.W, wl.stride
+    need = W * S * (8 + wl.theta_bytes) + (2 << 30)
+    free, _ = torch.cuda.mem_get_info()
+    if need > free:
+        pytest.skip(f"{name}: needs {need / 1e9:.0f} GB, {free / 1e9:.0f} GB free")
+    print(f"[case] {name}: W={W} P={wl.P} tensors={len(wl.tensors)} theta={wl.theta_dtype}", flush=True)
+    dev = torch.device("cuda")
+    tdt = torch.float32 if wl.theta_dtype == "f32" else torch.bfloat16
+    phi = torch.empty((W, S), dtype=torch.float32, device=dev)
+    delta = torch.zeros((W, S), dtype=torch.float32, device=dev)
+    theta = torch.empty((W, S), dtype=tdt, device=dev)
+    workloads.fill_phi0_device(phi, wl.seed, wl.init_std)
+
+    cols = workloads.column_sample(wl, strided)
+    cols_t = torch.from_numpy(cols).to(dev)
+    gaps = gap_columns(wl)
+    gaps_t = torch.from_numpy(gaps).to(dev)
+    if len(gaps):
+        phi[:, gaps_t] = float("nan")
+        delta[:, gaps_t] = float("nan")
+
+    # oracle state on the sampled columns, as one dense arena
+    o_phi = phi[:, cols_t].cpu().numpy()
+    o_delta = np.zeros_like(o_phi)
+    plan = nl.LaunchPlan(phi, delta, theta, S, W, nl.F32 if wl.theta_dtype == "f32" else nl.BF16, wl.segments)
+    info = plan.info()
+    assert info["elements_per_worker"] == wl.P
+    assert info["num_runs"] == (1 if name != "ragged_gapped" else len(wl.tensors))
+    hp = (wl.alpha, wl.beta, wl.gamma)
+
+    for t in range(steps):
+        workloads.fake_inner_phase_device(theta, phi, wl.seed, t, wl.sigma)
+        o_theta = workloads.fake_inner_phase_cpu(o_phi, wl.seed, t, wl.sigma, wl.theta_dtype)
+        theta[:, cols_t] = theta_to_device(np.ascontiguousarray(o_theta), dev)
+        if len(gaps):
+            theta[:, gaps_t] = float("nan")
+        n = wl.n_at(t)
+        members, offsets = nl.plan_groups(wl.seed, t, W, n)
+        om, oo = oracle.plan_groups(wl.seed, t, W, n)
+        assert members.tolist() == om.tolist() and offsets.tolist() == oo.tolist()
+        nl.outer_step(plan, phi, delta, theta, hp, members, offsets)
+        oracle.outer_step_f32(o_phi, o_delta, o_theta, hp, om, oo)
+        torch.cuda.synchronize()
+        got = {"phi": phi[:, cols_t].cpu().numpy(), "delta": delta[:, cols_t].cpu().numpy(),
+               "theta": to_bits(theta[:, cols_t].cpu())}
+        want = {"phi": o_phi, "delta": o_delta, "theta": o_theta}
+        assert_state_equal(got, want, f"{name} step {t} (n={n})", wl.theta_dtype)
+        if len(gaps):
+            assert bool(torch.isnan(phi[:, gaps_t]).all()) and bool(torch.isnan(delta[:, gaps_t]).all())
+            assert bool(torch.isnan(theta[:, gaps_t].float()).all())
+        # properties that hold at any size, checked on the whole arena: the restart makes the fast
+        # weights equal the (rounded) slow weights everywhere, and nothing overflowed
+        if t == steps - 1:
+            for w in range(0, W, max(1, W // 4)):
+                row_phi = phi[w]
+                if len(gaps):
+                    row_phi = torch.nan_to_num(row_phi, nan=0.0)
+                    assert torch.equal(torch.nan_to_num(theta[w].float(), nan=0.0), row_phi.to(tdt).float())
+                else:
+                    assert torch.equal(theta[w], row_phi.to(tdt))
+                assert bool(torch.isfinite(row_phi).all())
+    print(f"[done] {name}: {steps} steps, {len(cols)} sampled columns x {W} workers bit-identical", flush=True)
+    plan.destroy()
+    del phi, delta, theta
+    torch.cuda.empty_cache()

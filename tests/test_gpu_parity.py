@@ -43,18 +43,19 @@ def test_small_arena_multi_step(theta_dtype, layout, n):
 @pytest.mark.parametrize("theta_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("vpt", [1, 2, 4])
 @pytest.mark.parametrize("nontemporal", [0, 1])
-@pytest.mark.parametrize("group_major", [0, 1])
-def test_launch_shapes_do_not_change_results(theta_dtype, vpt, nontemporal, group_major):
+@pytest.mark.parametrize("group_major,xcd_map", [(0, 0), (1, 0), (0, 1), (1, 1), (1, 2), (0, 5), (1, 64), (1, 4096)])
+def test_launch_shapes_do_not_change_results(theta_dtype, vpt, nontemporal, group_major, xcd_map):
     wl = workloads.make_small(theta_dtype=theta_dtype, W=16, n_schedule=(2, 4, 8, 1), layout="gapped",
                               total=400_000)
     case = SmallCase(wl, nl)
-    case.plan.tune(vectors_per_thread=vpt, nontemporal=nontemporal, group_major=group_major)
+    case.plan.tune(vectors_per_thread=vpt, nontemporal=nontemporal, group_major=group_major,
+                   xcd_map=xcd_map)
     assert case.plan.info()["tile_elems"] == 1024 * vpt
     for t in range(4):
         case.inner_phase(t)
         members, offsets = nl.plan_groups(wl.seed, t, wl.W, wl.n_at(t))
         case.step(t, members, offsets)
-        case.check(f"vpt={vpt} nt={nontemporal} gm={group_major} step {t}")
+        case.check(f"vpt={vpt} nt={nontemporal} gm={group_major} xm={xcd_map} step {t}")
 
 
 @pytest.mark.parametrize("theta_dtype", ["f32", "bf16"])
