@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--vectors-per-thread", type=int, default=-1)
     ap.add_argument("--nontemporal", type=int, default=-1)
     ap.add_argument("--group-major", type=int, default=-1)
+    ap.add_argument("--xcd-map", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-inner-phase", action="store_true",
                     help="skip the untimed re-draw of theta between steps (for profiler runs)")
@@ -140,7 +141,7 @@ def main():
     theta = torch.empty((W, S), dtype=tdt, device=dev)
     workloads.fill_phi0_device(phi, wl.seed, wl.init_std)
     plan = nl.LaunchPlan(phi, delta, theta, S, W, nl.F32 if wl.theta_dtype == "f32" else nl.BF16, wl.segments)
-    plan.tune(args.vectors_per_thread, args.nontemporal, args.group_major)
+    plan.tune(args.vectors_per_thread, args.nontemporal, args.group_major, args.xcd_map)
     n_of = (lambda t: args.subgroup) if args.subgroup else wl.n_at
 
     ev0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
@@ -175,18 +176,25 @@ def main():
     alg_bytes = updates * wl.bytes_per_update             # per launch: one launch covers the whole arena
     achieved = alg_bytes / avg_kernel_s / 1e9
 
-    # yardstick: a plain copy kernel over the momentum array (its contents are no longer needed)
+    # yardsticks: plain streaming kernels over the momentum array (its contents are no longer needed)
     half = (W // 2) * S * 4 // 16 * 16
-    copy_gbps = None
+    probes = {"copy": None, "read": None, "fill": None}
     if half >= (1 << 24):
-        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        nl.copy_probe(delta.data_ptr() + half, delta, half)
-        c0.record()
-        for _ in range(3):
-            nl.copy_probe(delta.data_ptr() + half, delta, half)
-        c1.record()
-        torch.cuda.synchronize()
-        copy_gbps = 3 * 2 * half / (c0.elapsed_time(c1) / 1e3) / 1e9
+        sink = torch.zeros(4, dtype=torch.float32, device=dev)
+        runs = {
+            "copy": (lambda: nl.copy_probe(delta.data_ptr() + half, delta, half), 2 * half),
+            "read": (lambda: nl.read_probe(delta, 2 * half, sink), 2 * half),
+            "fill": (lambda: nl.fill_probe(delta, 2 * half, 0.0), 2 * half),
+        }
+        for name, (fn, nbytes) in runs.items():
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            fn()
+            c0.record()
+            for _ in range(3):
+                fn()
+            c1.record()
+            torch.cuda.synchronize()
+            probes[name] = 3 * nbytes / (c0.elapsed_time(c1) / 1e3) / 1e9
 
     out = {
         "metric": "outer-step worker-param updates/s",
@@ -210,7 +218,8 @@ def main():
             "algorithmic_bytes_per_launch": alg_bytes,
             "bytes_per_update": wl.bytes_per_update,
             "avg_kernel_ms": avg_kernel_s * 1e3, "min_kernel_ms": min(kernel_ms), "max_kernel_ms": max(kernel_ms),
-            "copy_probe_GBps": copy_gbps,
+            "copy_probe_GBps": probes["copy"], "read_probe_GBps": probes["read"],
+            "fill_probe_GBps": probes["fill"],
         },
         "host": {"plan_groups_us": float(np.median(plan_us)),
                  "step_minus_kernel_ms": ms_per_step - avg_kernel_s * 1e3},

@@ -142,9 +142,11 @@ noloco_status noloco_launch_plan_info(const noloco_launch_plan* plan, int64_t* e
                                       int32_t* num_runs, int64_t* num_tiles, int32_t* tile_elems);
 
 /*
- * Launch-shape knobs; the defaults are the measured best on MI355X.  Results never depend
- * on them, only speed does.  A field set to -1 keeps its current value.
- *   vectors_per_thread  16-byte vectors each thread handles per tile: 1, 2 or 4
+ * Launch-shape knobs.  Results never depend on them, only speed does.  Every field set to
+ * -1 means "automatic": the library picks the measured best for MI355X per subgroup size
+ * (the state of a new plan).  The call replaces all four fields.
+ *   vectors_per_thread  16-byte vectors each thread handles per tile: 1, 2 or 4 (subgroups of
+ *                       4 use at most 2, larger ones 1, to stay within the register file)
  *   nontemporal         1 = streaming (non-temporal) loads and stores, 0 = ordinary
  *   group_major         1 = consecutive work items walk the tiles of one group,
  *                       0 = consecutive work items take the same tile of successive groups
@@ -190,13 +192,21 @@ noloco_status noloco_outer_step(const noloco_launch_plan* plan, const noloco_are
                                 void* hip_stream);
 
 /*
- * Measurement aid, not part of the method: a plain device-to-device copy kernel of
- * `bytes` bytes (a multiple of 16; both pointers 16-byte aligned) on `hip_stream`.
- * Harnesses use it as the "achievable bandwidth" yardstick and to calibrate the
- * profiler's HBM byte counters against a transfer of known size.
+ * Measurement aids, not part of the method: plain streaming kernels over `bytes` bytes (a
+ * multiple of 16; pointers 16-byte aligned) on `hip_stream`, with the same non-temporal
+ * 16-byte accesses as the outer step.  Harnesses use them as yardsticks for what the chip's
+ * HBM delivers to pure reads, pure writes and a 1:1 copy, and to calibrate the profiler's
+ * HBM byte counters against a transfer of known size.
+ *   noloco_copy_probe  dst[i] = src[i]
+ *   noloco_read_probe  reads src and writes nothing (sink_device: 4 writable bytes that are
+ *                      only written if the data folds to a pattern no real data produces)
+ *   noloco_fill_probe  dst[i] = value
  */
 noloco_status noloco_copy_probe(void* dst_device, const void* src_device, int64_t bytes,
                                 void* hip_stream);
+noloco_status noloco_read_probe(const void* src_device, int64_t bytes, void* sink_device,
+                                void* hip_stream);
+noloco_status noloco_fill_probe(void* dst_device, int64_t bytes, float value, void* hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char* noloco_strerror(noloco_status status);

@@ -73,6 +73,10 @@ def _load():
                                     C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     L.noloco_copy_probe.restype = C.c_int
     L.noloco_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    L.noloco_read_probe.restype = C.c_int
+    L.noloco_read_probe.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+    L.noloco_fill_probe.restype = C.c_int
+    L.noloco_fill_probe.argtypes = [C.c_void_p, C.c_int64, C.c_float, C.c_void_p]
     L.noloco_strerror.restype = C.c_char_p
     L.noloco_strerror.argtypes = [C.c_int]
     return L
@@ -82,7 +86,8 @@ _lib = _load()
 
 EXPORTS = ("noloco_plan_groups", "noloco_merge_segments", "noloco_launch_plan_create",
            "noloco_launch_plan_destroy", "noloco_launch_plan_info", "noloco_launch_plan_tune",
-           "noloco_outer_step", "noloco_copy_probe", "noloco_strerror")
+           "noloco_outer_step", "noloco_copy_probe", "noloco_read_probe", "noloco_fill_probe",
+           "noloco_strerror")
 
 
 def library_path() -> str:
@@ -192,3 +197,15 @@ def copy_probe(dst, src, nbytes: int, stream=None):
     """noloco_copy_probe: plain device copy of nbytes (measurement aid)."""
     _check(_lib.noloco_copy_probe(_ptr(dst), _ptr(src), int(nbytes), _stream(stream)),
            "noloco_copy_probe")
+
+
+def read_probe(src, nbytes: int, sink, stream=None):
+    """noloco_read_probe: streams nbytes from src, writes nothing (measurement aid)."""
+    _check(_lib.noloco_read_probe(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)),
+           "noloco_read_probe")
+
+
+def fill_probe(dst, nbytes: int, value: float = 0.0, stream=None):
+    """noloco_fill_probe: streams nbytes of `value` into dst (measurement aid)."""
+    _check(_lib.noloco_fill_probe(_ptr(dst), int(nbytes), float(value), _stream(stream)),
+           "noloco_fill_probe")

@@ -17,6 +17,19 @@ using noloco::Span;
 
 constexpr int32_t kTileSizes[3] = {1024, 2048, 4096};  // kBlockThreads * kVecElems * {1, 2, 4}
 
+// Launch shape for subgroup size n: the caller's explicit choices, else the measured best on
+// MI355X.  Pairs stream best with big tiles walked group by group; larger subgroups have
+// smaller tiles, which want each XCD on a contiguous range (all 16 of its L2 channels busy)
+// and all groups in flight at once.
+noloco::KernelChoice resolve(const noloco::KernelChoice& asked, int32_t n) {
+  noloco::KernelChoice c = asked;
+  if (c.vectors_per_thread == -1) c.vectors_per_thread = 4;
+  if (c.nontemporal == -1) c.nontemporal = 1;
+  if (c.group_major == -1) c.group_major = n <= 2 ? 1 : 0;
+  if (c.xcd_map == -1) c.xcd_map = n <= 2 ? 0 : 1;
+  return c;
+}
+
 bool aligned(const void* p, uintptr_t bytes) {
   return (reinterpret_cast<uintptr_t>(p) % bytes) == 0;
 }
@@ -33,7 +46,7 @@ struct noloco_launch_plan {
   Span* dev_spans = nullptr;                 // one allocation holding the three tables
   int64_t table_offset[3] = {0, 0, 0};       // entry index of each table inside dev_spans
   int64_t tiles[3] = {0, 0, 0};              // tiles per group for each tile size
-  noloco::KernelChoice choice{2, 1, 1, 1};
+  noloco::KernelChoice choice{-1, -1, -1, -1};   // -1 = chosen per launch, see resolve()
 };
 
 extern "C" noloco_status noloco_launch_plan_create(const noloco_arena* arena,
@@ -98,26 +111,12 @@ extern "C" noloco_status noloco_launch_plan_destroy(noloco_launch_plan* plan) {
 extern "C" noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan,
                                                  const noloco_tuning* tuning) {
   if (plan == nullptr || tuning == nullptr) return NOLOCO_ERR_NULL;
-  noloco::KernelChoice c = plan->choice;
-  if (tuning->vectors_per_thread != -1) {
-    if (tuning->vectors_per_thread != 1 && tuning->vectors_per_thread != 2 &&
-        tuning->vectors_per_thread != 4)
-      return NOLOCO_ERR_INVALID_ARG;
-    c.vectors_per_thread = tuning->vectors_per_thread;
-  }
-  if (tuning->nontemporal != -1) {
-    if (tuning->nontemporal != 0 && tuning->nontemporal != 1) return NOLOCO_ERR_INVALID_ARG;
-    c.nontemporal = tuning->nontemporal;
-  }
-  if (tuning->group_major != -1) {
-    if (tuning->group_major != 0 && tuning->group_major != 1) return NOLOCO_ERR_INVALID_ARG;
-    c.group_major = tuning->group_major;
-  }
-  if (tuning->xcd_map != -1) {
-    if (tuning->xcd_map < 0 || tuning->xcd_map > 4096) return NOLOCO_ERR_INVALID_ARG;
-    c.xcd_map = tuning->xcd_map;
-  }
-  plan->choice = c;
+  const int32_t v = tuning->vectors_per_thread;
+  if (v != -1 && v != 1 && v != 2 && v != 4) return NOLOCO_ERR_INVALID_ARG;
+  if (tuning->nontemporal < -1 || tuning->nontemporal > 1) return NOLOCO_ERR_INVALID_ARG;
+  if (tuning->group_major < -1 || tuning->group_major > 1) return NOLOCO_ERR_INVALID_ARG;
+  if (tuning->xcd_map < -1 || tuning->xcd_map > 4096) return NOLOCO_ERR_INVALID_ARG;
+  plan->choice = noloco::KernelChoice{v, tuning->nontemporal, tuning->group_major, tuning->xcd_map};
   return NOLOCO_OK;
 }
 
@@ -125,7 +124,7 @@ extern "C" noloco_status noloco_launch_plan_info(const noloco_launch_plan* plan,
                                                  int64_t* elements_per_worker, int32_t* num_runs,
                                                  int64_t* num_tiles, int32_t* tile_elems) {
   if (plan == nullptr) return NOLOCO_ERR_NULL;
-  const int32_t te = noloco::tile_elems_for(2, plan->choice.vectors_per_thread);
+  const int32_t te = noloco::tile_elems_for(2, resolve(plan->choice, 2).vectors_per_thread);
   int t = 0;
   while (kTileSizes[t] != te) ++t;
   if (elements_per_worker) *elements_per_worker = plan->elements;
@@ -190,13 +189,14 @@ extern "C" noloco_status noloco_outer_step(const noloco_launch_plan* plan, const
   args.alpha = hparams->alpha;
   args.beta = hparams->beta;
   args.gamma = hparams->gamma;
-  args.group_major = plan->choice.group_major;
-  args.xcd_map = plan->choice.xcd_map;
 
   for (const auto& kv : by_size) {
     const int32_t n = kv.first;
     const std::vector<int32_t>& list = kv.second;
-    const int32_t te = noloco::tile_elems_for(n, plan->choice.vectors_per_thread);
+    const noloco::KernelChoice choice = resolve(plan->choice, n);
+    args.group_major = choice.group_major;
+    args.xcd_map = choice.xcd_map;
+    const int32_t te = noloco::tile_elems_for(n, choice.vectors_per_thread);
     int t = 0;
     while (kTileSizes[t] != te) ++t;
     args.spans = plan->dev_spans + plan->table_offset[t];
@@ -215,7 +215,7 @@ extern "C" noloco_status noloco_outer_step(const noloco_launch_plan* plan, const
       args.num_groups = static_cast<int32_t>(count);
       args.work_items = static_cast<uint32_t>(args.num_tiles * count);
       std::memcpy(args.rows, list.data() + g0 * n, static_cast<size_t>(count * n) * sizeof(int32_t));
-      if (noloco::launch_outer_step(args, plan->theta_dtype, plan->choice, hip_stream) != 0)
+      if (noloco::launch_outer_step(args, plan->theta_dtype, choice, hip_stream) != 0)
         return NOLOCO_ERR_DEVICE;
     }
   }
@@ -228,8 +228,28 @@ extern "C" noloco_status noloco_copy_probe(void* dst_device, const void* src_dev
   if (bytes < 0 || bytes % 16 != 0) return NOLOCO_ERR_INVALID_ARG;
   if (!aligned(dst_device, 16) || !aligned(src_device, 16)) return NOLOCO_ERR_ALIGNMENT;
   if (bytes == 0) return NOLOCO_OK;
-  return noloco::launch_copy_probe(dst_device, src_device, bytes, hip_stream) == 0 ? NOLOCO_OK
-                                                                                   : NOLOCO_ERR_DEVICE;
+  return noloco::launch_stream_probe(0, dst_device, src_device, bytes, 0.f, hip_stream) == 0
+             ? NOLOCO_OK : NOLOCO_ERR_DEVICE;
+}
+
+extern "C" noloco_status noloco_read_probe(const void* src_device, int64_t bytes, void* sink_device,
+                                           void* hip_stream) {
+  if (src_device == nullptr || sink_device == nullptr) return NOLOCO_ERR_NULL;
+  if (bytes < 0 || bytes % 16 != 0) return NOLOCO_ERR_INVALID_ARG;
+  if (!aligned(src_device, 16) || !aligned(sink_device, 4)) return NOLOCO_ERR_ALIGNMENT;
+  if (bytes == 0) return NOLOCO_OK;
+  return noloco::launch_stream_probe(1, sink_device, src_device, bytes, 0.f, hip_stream) == 0
+             ? NOLOCO_OK : NOLOCO_ERR_DEVICE;
+}
+
+extern "C" noloco_status noloco_fill_probe(void* dst_device, int64_t bytes, float value,
+                                           void* hip_stream) {
+  if (dst_device == nullptr) return NOLOCO_ERR_NULL;
+  if (bytes < 0 || bytes % 16 != 0) return NOLOCO_ERR_INVALID_ARG;
+  if (!aligned(dst_device, 16)) return NOLOCO_ERR_ALIGNMENT;
+  if (bytes == 0) return NOLOCO_OK;
+  return noloco::launch_stream_probe(2, dst_device, nullptr, bytes, value, hip_stream) == 0
+             ? NOLOCO_OK : NOLOCO_ERR_DEVICE;
 }
 
 extern "C" const char* noloco_strerror(noloco_status status) {

@@ -322,19 +322,48 @@ __global__ void __launch_bounds__(kBlockThreads) copy_probe_kernel(f4* __restric
   }
 }
 
+// Read-only and write-only counterparts of the copy probe (same grid shape).  The read probe
+// folds what it loads into a value that is stored only if it equals a pattern the data never
+// produces, so the loads cannot be optimised away and nothing is written.
+__global__ void __launch_bounds__(kBlockThreads) read_probe_kernel(const f4* __restrict__ src,
+                                                                   int64_t vectors, float* sink) {
+  const int64_t first = static_cast<int64_t>(blockIdx.x) * (kBlockThreads * 4) + threadIdx.x;
+  f4 acc = {0.f, 0.f, 0.f, 0.f};
+  f4 v[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = first + u * kBlockThreads;
+    v[u] = i < vectors ? __builtin_nontemporal_load(src + i) : acc;
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) acc = acc + v[u];
+  if (acc.x == 1.2345e-30f && acc.y == -5.4321e-30f) *sink = acc.z;
+}
+
+__global__ void __launch_bounds__(kBlockThreads) fill_probe_kernel(f4* __restrict__ dst,
+                                                                   int64_t vectors, float value) {
+  const int64_t first = static_cast<int64_t>(blockIdx.x) * (kBlockThreads * 4) + threadIdx.x;
+  const f4 v = {value, value, value, value};
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = first + u * kBlockThreads;
+    if (i < vectors) __builtin_nontemporal_store(v, dst + i);
+  }
+}
+
 template <int N, typename Tag, int U>
-hipError_t launch_fixed_nt(const StepArgs& args, bool nt, dim3 grid, hipStream_t s) {
-  if (nt) hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, true>), grid, dim3(kBlockThreads), 0, s, args);
-  else    hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, false>), grid, dim3(kBlockThreads), 0, s, args);
+hipError_t launch_fixed_nt(const StepArgs& args, bool nt, dim3 grid, unsigned lds, hipStream_t s) {
+  if (nt) hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, true>), grid, dim3(kBlockThreads), lds, s, args);
+  else    hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, false>), grid, dim3(kBlockThreads), lds, s, args);
   return hipGetLastError();
 }
 
 template <int N, typename Tag>
-hipError_t launch_fixed(const StepArgs& args, int u, bool nt, dim3 grid, hipStream_t s) {
+hipError_t launch_fixed(const StepArgs& args, int u, bool nt, dim3 grid, unsigned lds, hipStream_t s) {
   constexpr int kMaxU = N <= 2 ? 4 : (N == 4 ? 2 : 1);
-  if constexpr (kMaxU >= 4) if (u == 4) return launch_fixed_nt<N, Tag, 4>(args, nt, grid, s);
-  if constexpr (kMaxU >= 2) if (u == 2) return launch_fixed_nt<N, Tag, 2>(args, nt, grid, s);
-  return launch_fixed_nt<N, Tag, 1>(args, nt, grid, s);
+  if constexpr (kMaxU >= 4) if (u == 4) return launch_fixed_nt<N, Tag, 4>(args, nt, grid, lds, s);
+  if constexpr (kMaxU >= 2) if (u == 2) return launch_fixed_nt<N, Tag, 2>(args, nt, grid, lds, s);
+  return launch_fixed_nt<N, Tag, 1>(args, nt, grid, lds, s);
 }
 
 template <typename Tag>
@@ -348,16 +377,17 @@ hipError_t launch_for_dtype(const StepArgs& args, const KernelChoice& choice, hi
     wgs = (wgs + round - 1) / round * round;
   }
   const dim3 grid(wgs);
+  const unsigned lds = 0;
   switch (args.n) {
-    case 1: return launch_fixed<1, Tag>(args, u, nt, grid, s);
-    case 2: return launch_fixed<2, Tag>(args, u, nt, grid, s);
-    case 4: return launch_fixed<4, Tag>(args, u, nt, grid, s);
-    case 8: return launch_fixed<8, Tag>(args, u, nt, grid, s);
-    case 16: return launch_fixed<16, Tag>(args, u, nt, grid, s);
+    case 1: return launch_fixed<1, Tag>(args, u, nt, grid, lds, s);
+    case 2: return launch_fixed<2, Tag>(args, u, nt, grid, lds, s);
+    case 4: return launch_fixed<4, Tag>(args, u, nt, grid, lds, s);
+    case 8: return launch_fixed<8, Tag>(args, u, nt, grid, lds, s);
+    case 16: return launch_fixed<16, Tag>(args, u, nt, grid, lds, s);
     default: break;
   }
-  if (nt) hipLaunchKernelGGL((outer_step_generic<Tag, true>), grid, dim3(kBlockThreads), 0, s, args);
-  else    hipLaunchKernelGGL((outer_step_generic<Tag, false>), grid, dim3(kBlockThreads), 0, s, args);
+  if (nt) hipLaunchKernelGGL((outer_step_generic<Tag, true>), grid, dim3(kBlockThreads), lds, s, args);
+  else    hipLaunchKernelGGL((outer_step_generic<Tag, false>), grid, dim3(kBlockThreads), lds, s, args);
   return hipGetLastError();
 }
 
@@ -383,14 +413,22 @@ int launch_outer_step(const StepArgs& args, int32_t theta_dtype, const KernelCho
   return static_cast<int>(e);
 }
 
-int launch_copy_probe(void* dst, const void* src, int64_t bytes, void* stream) {
+int launch_stream_probe(int mode, void* dst, const void* src, int64_t bytes, float value,
+                        void* stream) {
   const int64_t vectors = bytes / 16;
   const int64_t per_block = kBlockThreads * 4;
   const int64_t blocks = (vectors + per_block - 1) / per_block;
   if (blocks > 0x7FFFFFFFll) return static_cast<int>(hipErrorInvalidValue);
-  hipLaunchKernelGGL(copy_probe_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kBlockThreads), 0,
-                     static_cast<hipStream_t>(stream), static_cast<f4*>(dst),
-                     static_cast<const f4*>(src), vectors);
+  const dim3 grid(static_cast<uint32_t>(blocks)), block(kBlockThreads);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (mode == 0)
+    hipLaunchKernelGGL(copy_probe_kernel, grid, block, 0, s, static_cast<f4*>(dst),
+                       static_cast<const f4*>(src), vectors);
+  else if (mode == 1)
+    hipLaunchKernelGGL(read_probe_kernel, grid, block, 0, s, static_cast<const f4*>(src), vectors,
+                       static_cast<float*>(dst));
+  else
+    hipLaunchKernelGGL(fill_probe_kernel, grid, block, 0, s, static_cast<f4*>(dst), vectors, value);
   return static_cast<int>(hipGetLastError());
 }
 

@@ -59,7 +59,8 @@ int64_t build_spans(const std::vector<noloco_segment>& runs, int32_t tile_elems,
 // kernels.hip: enqueue one launch.  Returns hipError_t as int.
 int launch_outer_step(const StepArgs& args, int32_t theta_dtype, const KernelChoice& choice,
                       void* stream);
-int launch_copy_probe(void* dst, const void* src, int64_t bytes, void* stream);
+// mode 0 copy, 1 read only (dst = 4-byte sink), 2 fill
+int launch_stream_probe(int mode, void* dst, const void* src, int64_t bytes, float value, void* stream);
 
 // tile size in elements for a kernel choice and group size
 int32_t tile_elems_for(int32_t n, int32_t vectors_per_thread);

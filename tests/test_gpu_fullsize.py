@@ -17,7 +17,9 @@ from harness import assert_state_equal, theta_to_device, to_bits
 
 pytestmark = pytest.mark.gpu
 
-nl = pytest.importorskip("paper_2506_10911_amd", reason="libnoloco.so not built")
+import paper_2506_10911_amd as nl
+
+nl.library_path()          # loads libnoloco.so now; a missing library is an error, not a skip
 
 CASES = [
     # name, steps compared, strided sample size

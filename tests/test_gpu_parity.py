@@ -12,7 +12,9 @@ from harness import SmallCase, assert_state_equal, to_bits
 
 pytestmark = pytest.mark.gpu
 
-nl = pytest.importorskip("paper_2506_10911_amd", reason="libnoloco.so not built")
+import paper_2506_10911_amd as nl
+
+nl.library_path()          # loads libnoloco.so now; a missing library is an error, not a skip
 
 
 def groups_from_lists(lists):
@@ -271,9 +273,37 @@ def test_stream_argument_is_honoured():
     case.check("side stream")
 
 
-def test_copy_probe_copies():
+def test_probes():
     src = torch.arange(1 << 20, dtype=torch.float32, device="cuda")
     dst = torch.zeros_like(src)
     nl.copy_probe(dst, src, src.numel() * 4 - 16)
     torch.cuda.synchronize()
     assert torch.equal(dst[:-4], src[:-4]) and float(dst[-4:].abs().sum()) == 0.0
+    sink = torch.full((4,), 7.0, device="cuda")
+    nl.read_probe(src, src.numel() * 4 - 16, sink)
+    nl.fill_probe(dst, dst.numel() * 4 - 32, 2.5)
+    torch.cuda.synchronize()
+    assert bool((sink == 7.0).all())                            # the read probe writes nothing
+    assert bool((dst[:-8] == 2.5).all()) and torch.equal(dst[-8:-4], src[-8:-4])
+    for fn in (lambda: nl.copy_probe(dst, src, 24), lambda: nl.fill_probe(dst, -16),
+               lambda: nl.read_probe(src, 20, sink)):
+        with pytest.raises(nl.NolocoError) as e:
+            fn()
+        assert e.value.status == 2
+    with pytest.raises(nl.NolocoError) as e:
+        nl.fill_probe(dst.data_ptr() + 4, 16)
+    assert e.value.status == 5
+
+
+def test_tuning_is_validated_and_automatic_by_default():
+    wl = workloads.make_small(W=8, layout="tight", count=4, total=3000)
+    case = SmallCase(wl, nl, canary=False)
+    assert case.plan.info()["tile_elems"] == 4096              # automatic: 4 vectors per thread for pairs
+    for bad in [dict(vectors_per_thread=3), dict(nontemporal=2), dict(group_major=-2), dict(xcd_map=4097)]:
+        with pytest.raises(nl.NolocoError) as e:
+            case.plan.tune(**bad)
+        assert e.value.status == 2
+    case.plan.tune(vectors_per_thread=1)
+    assert case.plan.info()["tile_elems"] == 1024
+    case.plan.tune()                                           # back to automatic
+    assert case.plan.info()["tile_elems"] == 4096

@@ -10,7 +10,9 @@ import pytest
 import oracle
 from conftest import ROOT
 
-nl = pytest.importorskip("paper_2506_10911_amd", reason="libnoloco.so not built")
+import paper_2506_10911_amd as nl
+
+nl.library_path()          # loads libnoloco.so now; a missing library is an error, not a skip
 
 
 def declared_symbols():
