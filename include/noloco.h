@@ -183,8 +183,9 @@ noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan, const noloco_tun
  * groups are ignored; a group larger than NOLOCO_MAX_GROUP gives NOLOCO_ERR_UNSUPPORTED.
  * The result does not depend on the order of members inside a group nor on the order of
  * the groups (sums run in ascending worker id), and is bit-identical from run to run.
- * Subgroup sizes 1, 2, 4, 8 and 16 take register-resident kernels that move each byte
- * once; other sizes take a two-pass kernel that reads phi twice.
+ * Subgroup sizes 1, 2, 4, 8, 16 (everything in registers) and 32, 64 (phi in registers) move
+ * each byte once; other sizes take a two-pass kernel that reads phi twice (the second read
+ * normally hits in cache).
  */
 noloco_status noloco_outer_step(const noloco_launch_plan* plan, const noloco_arena* arena,
                                 const noloco_hparams* hparams, const int32_t* members,

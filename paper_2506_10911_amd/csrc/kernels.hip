@@ -255,37 +255,137 @@ __global__ void __launch_bounds__(kBlockThreads) outer_step_fixed(const StepArgs
 }
 
 // Two passes over the members for a group size only known at run time: the first forms the
-// two sums, the second re-reads phi, reads delta and writes.  V is f4 or float.
+// two sums, the second re-reads phi, reads delta and writes.  V is f4 or float.  Members are
+// taken four at a time with their loads issued together; the sums still run strictly in
+// ascending member order.
 template <typename Tag, typename V, bool NT>
 __device__ __forceinline__ void two_pass_at(const StepArgs& a, const int32_t* rows, int64_t c) {
   typedef ThetaMem<Tag, V> TM;
   typedef typename TM::elem TElem;
   typedef typename TM::mem TMem;
+  constexpr int kChunk = 4;
   const int n = a.n;
   TElem* const theta = static_cast<TElem*>(a.theta);
   int64_t at = static_cast<int64_t>(rows[0]) * a.stride + c;
-  V sum_P = *reinterpret_cast<const V*>(a.phi + at);
+  V sum_P = *reinterpret_cast<const V*>(a.phi + at);              // ordinary loads of phi: read again below
   V sum_D = sum_P - TM::widen(ld<NT>(reinterpret_cast<const TMem*>(theta + at)));
-  for (int j = 1; j < n; ++j) {
+  int j = 1;
+  for (; j + kChunk <= n; j += kChunk) {
+    V p[kChunk];
+    TMem t[kChunk];
+#pragma unroll
+    for (int k = 0; k < kChunk; ++k) {
+      at = static_cast<int64_t>(rows[j + k]) * a.stride + c;
+      p[k] = *reinterpret_cast<const V*>(a.phi + at);
+      t[k] = ld<NT>(reinterpret_cast<const TMem*>(theta + at));
+    }
+#pragma unroll
+    for (int k = 0; k < kChunk; ++k) {
+      sum_D = sum_D + (p[k] - TM::widen(t[k]));
+      sum_P = sum_P + p[k];
+    }
+  }
+  for (; j < n; ++j) {
     at = static_cast<int64_t>(rows[j]) * a.stride + c;
-    const V p = *reinterpret_cast<const V*>(a.phi + at);        // ordinary load: read again below
-    const V D = p - TM::widen(ld<NT>(reinterpret_cast<const TMem*>(theta + at)));
-    sum_D = sum_D + D;
+    const V p = *reinterpret_cast<const V*>(a.phi + at);
+    sum_D = sum_D + (p - TM::widen(ld<NT>(reinterpret_cast<const TMem*>(theta + at))));
     sum_P = sum_P + p;
   }
   const V mean_P = sum_P * a.inv_n;
   const V t2 = a.beta * (sum_D * a.inv_n);
-  for (int j = 0; j < n; ++j) {
-    at = static_cast<int64_t>(rows[j]) * a.stride + c;
-    const V p = ld<NT>(reinterpret_cast<const V*>(a.phi + at));
-    const V d = ld<NT>(reinterpret_cast<const V*>(a.delta + at));
+  auto finish = [&](int64_t where, V p, V d) {
     const V t1 = a.alpha * d;
     const V t3 = a.gamma * (p - mean_P);
     const V d_new = (t1 - t2) - t3;
     const V p_new = p + d_new;
-    st<NT>(reinterpret_cast<V*>(a.delta + at), d_new);
-    st<NT>(reinterpret_cast<V*>(a.phi + at), p_new);
-    st<NT>(reinterpret_cast<TMem*>(theta + at), TM::narrow(p_new));
+    st<NT>(reinterpret_cast<V*>(a.delta + where), d_new);
+    st<NT>(reinterpret_cast<V*>(a.phi + where), p_new);
+    st<NT>(reinterpret_cast<TMem*>(theta + where), TM::narrow(p_new));
+  };
+  j = 0;
+  for (; j + kChunk <= n; j += kChunk) {
+    V p[kChunk], d[kChunk];
+    int64_t where[kChunk];
+#pragma unroll
+    for (int k = 0; k < kChunk; ++k) {
+      where[k] = static_cast<int64_t>(rows[j + k]) * a.stride + c;
+      p[k] = ld<NT>(reinterpret_cast<const V*>(a.phi + where[k]));
+      d[k] = ld<NT>(reinterpret_cast<const V*>(a.delta + where[k]));
+    }
+#pragma unroll
+    for (int k = 0; k < kChunk; ++k) finish(where[k], p[k], d[k]);
+  }
+  for (; j < n; ++j) {
+    at = static_cast<int64_t>(rows[j]) * a.stride + c;
+    finish(at, ld<NT>(reinterpret_cast<const V*>(a.phi + at)),
+           ld<NT>(reinterpret_cast<const V*>(a.delta + at)));
+  }
+}
+
+// Subgroups of 32 or 64: too many members to keep phi, delta and theta of all of them in
+// registers, but phi alone fits (4 VGPRs per member).  First sweep: load phi and theta of every
+// member, keep phi, fold both sums.  Second sweep: load delta, finish, store.  Every byte is
+// still moved once.  Partial tiles fall back to the two-pass routine.
+template <int N, typename Tag, bool NT>
+__global__ void __launch_bounds__(kBlockThreads) outer_step_phi_resident(const StepArgs a) {
+  constexpr int kTile = kBlockThreads * kVecElems;
+  constexpr int kChunk = 8;
+  typedef ThetaMem<Tag, f4> TM;
+  typedef typename TM::elem TElem;
+  typedef typename TM::mem TMem;
+  TileRef tr;
+  if (!locate_tile(a, kTile, tr)) return;
+  const int32_t* rows = a.rows + tr.group * N;
+  const int64_t c = tr.base + static_cast<int64_t>(threadIdx.x) * kVecElems;
+  if (tr.c0 == tr.base && tr.c1 == tr.base + kTile) {
+    TElem* const theta = static_cast<TElem*>(a.theta);
+    f4 p[N];
+    f4 sum_D, sum_P;
+#pragma unroll
+    for (int j0 = 0; j0 < N; j0 += kChunk) {
+      TMem t[kChunk];
+#pragma unroll
+      for (int k = 0; k < kChunk; ++k) {
+        const int64_t at = static_cast<int64_t>(rows[j0 + k]) * a.stride + c;
+        p[j0 + k] = ld<NT>(reinterpret_cast<const f4*>(a.phi + at));
+        t[k] = ld<NT>(reinterpret_cast<const TMem*>(theta + at));
+      }
+#pragma unroll
+      for (int k = 0; k < kChunk; ++k) {
+        const f4 D = p[j0 + k] - TM::widen(t[k]);
+        if (j0 + k == 0) { sum_D = D; sum_P = p[0]; }
+        else { sum_D = sum_D + D; sum_P = sum_P + p[j0 + k]; }
+      }
+    }
+    const f4 mean_P = sum_P * a.inv_n;
+    const f4 t2 = a.beta * (sum_D * a.inv_n);
+#pragma unroll
+    for (int j0 = 0; j0 < N; j0 += kChunk) {
+      f4 d[kChunk];
+#pragma unroll
+      for (int k = 0; k < kChunk; ++k) {
+        const int64_t at = static_cast<int64_t>(rows[j0 + k]) * a.stride + c;
+        d[k] = ld<NT>(reinterpret_cast<const f4*>(a.delta + at));
+      }
+#pragma unroll
+      for (int k = 0; k < kChunk; ++k) {
+        const int64_t at = static_cast<int64_t>(rows[j0 + k]) * a.stride + c;
+        const f4 t1 = a.alpha * d[k];
+        const f4 t3 = a.gamma * (p[j0 + k] - mean_P);
+        const f4 d_new = (t1 - t2) - t3;
+        const f4 p_new = p[j0 + k] + d_new;
+        st<NT>(reinterpret_cast<f4*>(a.delta + at), d_new);
+        st<NT>(reinterpret_cast<f4*>(a.phi + at), p_new);
+        st<NT>(reinterpret_cast<TMem*>(theta + at), TM::narrow(p_new));
+      }
+    }
+    return;
+  }
+  if (c >= tr.c0 && c + kVecElems <= tr.c1) {
+    two_pass_at<Tag, f4, NT>(a, rows, c);
+  } else {
+    for (int e = 0; e < kVecElems; ++e)
+      if (c + e >= tr.c0 && c + e < tr.c1) two_pass_at<Tag, float, false>(a, rows, c + e);
   }
 }
 
@@ -384,6 +484,14 @@ hipError_t launch_for_dtype(const StepArgs& args, const KernelChoice& choice, hi
     case 4: return launch_fixed<4, Tag>(args, u, nt, grid, lds, s);
     case 8: return launch_fixed<8, Tag>(args, u, nt, grid, lds, s);
     case 16: return launch_fixed<16, Tag>(args, u, nt, grid, lds, s);
+    case 32:
+      if (nt) hipLaunchKernelGGL((outer_step_phi_resident<32, Tag, true>), grid, dim3(kBlockThreads), 0, s, args);
+      else    hipLaunchKernelGGL((outer_step_phi_resident<32, Tag, false>), grid, dim3(kBlockThreads), 0, s, args);
+      return hipGetLastError();
+    case 64:
+      if (nt) hipLaunchKernelGGL((outer_step_phi_resident<64, Tag, true>), grid, dim3(kBlockThreads), 0, s, args);
+      else    hipLaunchKernelGGL((outer_step_phi_resident<64, Tag, false>), grid, dim3(kBlockThreads), 0, s, args);
+      return hipGetLastError();
     default: break;
   }
   if (nt) hipLaunchKernelGGL((outer_step_generic<Tag, true>), grid, dim3(kBlockThreads), lds, s, args);

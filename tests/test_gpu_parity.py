@@ -43,6 +43,22 @@ def test_small_arena_multi_step(theta_dtype, layout, n):
 
 
 @pytest.mark.parametrize("theta_dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("layout", ["tight", "gapped"])
+@pytest.mark.parametrize("n", [32, 64, 128, 5])
+def test_large_subgroups(theta_dtype, layout, n):
+    """W = 640: subgroups of 32 and 64 (phi kept in registers), 128 and 5 (two passes)."""
+    W = 640
+    wl = workloads.make_small(theta_dtype=theta_dtype, W=W, n_schedule=(n,), layout=layout, count=8,
+                              total=20_000, steps=2)
+    case = SmallCase(wl, nl)
+    for t in range(wl.steps):
+        case.inner_phase(t)
+        members, offsets = nl.plan_groups(wl.seed, t, W, n)
+        case.step(t, members, offsets)
+        case.check(f"{wl.name} n={n} step {t}")
+
+
+@pytest.mark.parametrize("theta_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("vpt", [1, 2, 4])
 @pytest.mark.parametrize("nontemporal", [0, 1])
 @pytest.mark.parametrize("group_major,xcd_map", [(0, 0), (1, 0), (0, 1), (1, 1), (1, 2), (0, 5), (1, 64), (1, 4096)])
