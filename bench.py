@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD,
                     choices=["tiny", "gpt125m", "stage1p3b", "stage6p8b", "ragged_tight", "ragged_gapped"])
+    ap.add_argument("--op", default="outer_step", choices=["outer_step", "replica_spread"],
+                    help="outer_step (the headline path) or the read-only replica-spread pass over phi")
     ap.add_argument("--workers", type=int, default=0, help="override W (0 = the workload's own)")
     ap.add_argument("--subgroup", type=int, default=0, help="override the subgroup size n (0 = the workload's schedule)")
     ap.add_argument("--vectors-per-thread", type=int, default=-1)
@@ -104,6 +106,77 @@ def cpu_baseline(wl, n, hp):
     }
 
 
+def spread_cpu_baseline(wl):
+    """oracle.replica_spread (binary64 definition) on a bounded column sample, all W rows."""
+    import concurrent.futures as cf
+    import oracle
+    import workloads
+    cores = max(1, min(len(os.sched_getaffinity(0)), int(os.environ.get("OMP_NUM_THREADS", "16"))))
+    W = wl.W
+    cols = max(1 << 16, min((1 << 26) // W, wl.P))
+    cols -= cols % cores
+    x = np.tile(workloads.phi0_cpu(cols, wl.seed, wl.init_std), (W, 1)) + workloads.drift_cpu((W, cols), wl.seed, 0, wl.sigma)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    chunk = cols // cores
+    parts = [[(i * chunk, chunk)] for i in range(cores)]
+    pool = cf.ThreadPoolExecutor(cores)
+    oracle.replica_spread(x, [(0, 1 << 12)])
+    reps, t0 = 0, time.perf_counter()
+    while time.perf_counter() - t0 < 8.0:
+        list(pool.map(lambda seg: oracle.replica_spread(x, seg), parts))
+        reps += 1
+    dt = time.perf_counter() - t0
+    pool.shutdown()
+    return {"value": W * cols * reps / dt, "unit": "worker-params/s", "cores": cores, "kind": "oracle",
+            "sample": f"{cols} columns x all {W} workers of {wl.name}, {reps} passes on {cores} threads "
+                      "(disjoint column ranges of the same single-threaded routine)"}
+
+
+def run_replica_spread(args, wl, torch, nl, workloads, dev):
+    """K timed passes of noloco_replica_spread over the slow weights of the workload."""
+    W, S = wl.W, wl.stride
+    phi = torch.empty((W, S), dtype=torch.float32, device=dev)
+    workloads.fill_phi0_device(phi, wl.seed, wl.init_std)
+    workloads.fake_inner_phase_device(phi, phi, wl.seed, 0, wl.sigma)      # replicas drift apart
+    plan = nl.LaunchPlan(phi, phi, phi, S, W, nl.F32, wl.segments)
+    out = torch.zeros(len(wl.segments) + 1, dtype=torch.float64, device=dev)
+    kernel_ms, host_s = [], []
+    for t in range(args.warmup + args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        nl.replica_spread(plan, phi, nl.F32, out)
+        e1.record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        if t >= args.warmup:
+            host_s.append(t1 - t0)
+            kernel_ms.append(e0.elapsed_time(e1))
+    elems = W * wl.P
+    total_s = sum(host_s)
+    avg_s = sum(kernel_ms) / len(kernel_ms) / 1e3
+    achieved = elems * 4 / avg_s / 1e9
+    res = {
+        "metric": "replica-spread worker-params/s", "value": elems * args.steps / total_s,
+        "unit": "worker-params/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": total_s / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "W": W, "params_per_worker": wl.P, "tensors": len(wl.tensors),
+                   "array": "phi (f32)", "resident_GB": W * S * 4 / 1e9,
+                   "overall_std": float(out[-1]), "device": torch.cuda.get_device_name(0)},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "replica_spread_tiles (+ replica_spread_finish)",
+                     "algorithmic_bytes_per_launch": elems * 4, "bytes_per_update": 4,
+                     "avg_kernel_ms": avg_s * 1e3, "min_kernel_ms": min(kernel_ms), "max_kernel_ms": max(kernel_ms)},
+    }
+    del phi
+    torch.cuda.empty_cache()
+    res["cpu_baseline"] = None if args.no_cpu_baseline else spread_cpu_baseline(wl)
+    print(json.dumps(res))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -134,6 +207,9 @@ def main():
         wl.W = fit
     W, S = wl.W, wl.stride
     hp = (wl.alpha, wl.beta, wl.gamma)
+    if args.op == "replica_spread":
+        run_replica_spread(args, wl, torch, nl, workloads, dev)
+        return
 
     tdt = torch.float32 if wl.theta_dtype == "f32" else torch.bfloat16
     phi = torch.empty((W, S), dtype=torch.float32, device=dev)

@@ -25,7 +25,8 @@
  *     launch plan is created; "host" pointers are ordinary process memory;
  *   - GPU work is enqueued on the caller's stream and is NOT synchronised;
  *   - the library keeps no global state; a launch plan is immutable after creation
- *     (except through noloco_launch_plan_tune) and may be used from several threads.
+ *     (except through noloco_launch_plan_tune) and noloco_outer_step may use one plan from
+ *     several threads.
  */
 #ifndef NOLOCO_H_
 #define NOLOCO_H_
@@ -128,7 +129,8 @@ noloco_status noloco_merge_segments(const noloco_segment* segments, int32_t num_
 /*
  * Multi-tensor launch table.  Validates the arena layout (W, worker_stride, theta_dtype,
  * segments, alignment of the three base pointers), merges segments into runs, cuts runs
- * into tiles and uploads the table to the current device (one small hipMalloc, freed by
+ * into tiles and uploads the tables to the current device (one hipMalloc that also holds the
+ * scratch of noloco_replica_spread, 8 bytes per 1024 arena elements; freed by
  * noloco_launch_plan_destroy).  The plan depends on the layout only: the same plan serves
  * any three base pointers with the same layout.  Build once per arena, reuse every step.
  * On error *out is null.
@@ -191,6 +193,27 @@ noloco_status noloco_outer_step(const noloco_launch_plan* plan, const noloco_are
                                 const noloco_hparams* hparams, const int32_t* members,
                                 const int32_t* group_offsets, int32_t num_groups,
                                 void* hip_stream);
+
+/*
+ * Replica spread: how far the W replicas have drifted apart (results section of the paper,
+ * the figure plotting the standard deviation of the model weights across the data-parallel
+ * replicas, which the pull term of Eq. 2 is there to contain).  Read-only pass over one
+ * arena array x (phi, or theta):
+ *   per element k  v_k = (1/W) sum_w (x_w[k] - m_k)^2,  m_k = (1/W) sum_w x_w[k]   (all W rows)
+ *   per tensor s   out[s] = sqrt( mean over k in segment s of v_k )
+ *   overall        out[num_segments] = sqrt( mean over all segment elements of v_k )
+ * v_k is evaluated in binary32 (rows in ascending order: sum, mean = sum * (1/W), then the
+ * squared deviations summed in the same order, times 1/W); pooling over elements is in
+ * binary64 in a fixed order, so the result is bit-identical from run to run.
+ *   plan            launch plan of this layout (its W, worker_stride and segments are used)
+ *   x_device        device, [W][worker_stride] float or bf16 (x_dtype), NOLOCO_BASE_ALIGN_BYTES-aligned
+ *   out_std_device  device, out, double[num_segments + 1] in the order the segments were given
+ *                   at plan creation; an empty segment gives 0
+ * Enqueued on hip_stream, not synchronised.  The plan owns the scratch for the per-tile
+ * partial sums, so calls sharing one plan must not overlap in time.
+ */
+noloco_status noloco_replica_spread(const noloco_launch_plan* plan, const void* x_device,
+                                    int32_t x_dtype, double* out_std_device, void* hip_stream);
 
 /*
  * Measurement aids, not part of the method: plain streaming kernels over `bytes` bytes (a

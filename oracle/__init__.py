@@ -42,6 +42,9 @@ def load(path):
         C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
         C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_double, C.c_double,
         C.c_void_p, C.c_void_p, C.c_int32]
+    L.oracle_replica_spread.restype = C.c_int
+    L.oracle_replica_spread.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p,
+                                        C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
     return L
 
 
@@ -147,3 +150,22 @@ def outer_step_f64(phi, delta, theta, hp, members, group_offsets, segments=None)
         m.ctypes.data, o.ctypes.data, len(o) - 1)
     if rc != 0:
         raise ValueError("groups are not a partition of a subset of the workers")
+
+
+def replica_spread(x, segments=None, binary32=False):
+    """Pooled standard deviation across the W rows of x (float32 or bf16 bits as uint16, [W, stride]).
+
+    Returns float64 [num_segments + 1]: one value per segment, then the value over all segments.
+    binary32=False is the definition in binary64; True does the per-element arithmetic in binary32.
+    """
+    assert x.ndim == 2 and x.flags.c_contiguous and x.dtype in (np.float32, np.uint16)
+    W, stride = x.shape
+    off, ln = _segs(segments, stride)
+    assert ((off >= 0) & (off + ln <= stride)).all()
+    out = np.empty(len(off) + 1, dtype=np.float64)
+    rc = lib().oracle_replica_spread(x.ctypes.data, int(x.dtype == np.uint16), stride, W,
+                                     off.ctypes.data, ln.ctypes.data, len(off), int(binary32),
+                                     out.ctypes.data)
+    if rc != 0:
+        raise ValueError("bad arguments")
+    return out

@@ -37,6 +37,7 @@
 // -ffp-contract=off matters: the float instantiation is the bit-level target
 // and every operation below is meant to round once, separately.
 
+#include <cmath>
 #include <cstdint>
 #include <cstring>
 #include <vector>
@@ -165,6 +166,46 @@ void outer_step_impl(T* phi, T* delta, int64_t stride,
   }
 }
 
+// ---------------------------------------------------------------------------
+// Replica spread (results section, figure "standard deviation of the model
+// weights across the data parallel world size"): how far the W replicas of one
+// stage have drifted apart.  Per arena element k the population variance over
+// the W workers, v_k = (1/W) sum_w (x_w[k] - m_k)^2 with m_k = (1/W) sum_w x_w[k];
+// per tensor the pooled deviation sqrt(mean_k v_k); the same over all tensors.
+// (The paper fixes neither the 1/W vs 1/(W-1) convention nor how elements are
+// pooled into one number; these are this build's readings.)
+//   T = double: the definition.  T = float: the per-element arithmetic in
+//   binary32, in ascending worker order, as the GPU does it; pooling over
+//   elements is in double either way.
+// ---------------------------------------------------------------------------
+template <typename T, typename Load>
+void replica_spread_impl(Load load, int64_t stride, int32_t W,
+                         const int64_t* seg_off, const int64_t* seg_len, int32_t num_segments,
+                         double* out_std) {
+  const T inv_W = T(1) / T(static_cast<int64_t>(W));
+  double total = 0.0;
+  int64_t total_count = 0;
+  for (int32_t s = 0; s < num_segments; ++s) {
+    double pooled = 0.0;
+    for (int64_t k = seg_off[s]; k < seg_off[s] + seg_len[s]; ++k) {
+      T sum = load(k);
+      for (int32_t w = 1; w < W; ++w) sum = sum + load(static_cast<int64_t>(w) * stride + k);
+      const T mean = sum * inv_W;
+      T q = T(0);
+      for (int32_t w = 0; w < W; ++w) {
+        const T dev = load(static_cast<int64_t>(w) * stride + k) - mean;
+        const T sq = dev * dev;
+        q = (w == 0) ? sq : q + sq;
+      }
+      pooled += static_cast<double>(q * inv_W);
+    }
+    out_std[s] = seg_len[s] > 0 ? std::sqrt(pooled / static_cast<double>(seg_len[s])) : 0.0;
+    total += pooled;
+    total_count += seg_len[s];
+  }
+  out_std[num_segments] = total_count > 0 ? std::sqrt(total / static_cast<double>(total_count)) : 0.0;
+}
+
 bool groups_ok(const int32_t* members, const int32_t* group_offsets, int32_t num_groups, int32_t W) {
   if (num_groups < 0 || W < 1) return false;
   if (num_groups > 0 && (!members || !group_offsets)) return false;
@@ -268,6 +309,33 @@ int oracle_outer_step_f64(double* phi, double* delta, double* theta,
                           members, group_offsets, num_groups,
                           [theta](int64_t at) { return theta[at]; },
                           [theta](int64_t at, double v) { theta[at] = v; });
+  return 0;
+}
+
+// Replica spread of x ([W][stride] float, or bf16 bit patterns if x_is_bf16).
+// out_std: double[num_segments + 1]: pooled deviation per segment, then over all
+// segments.  arithmetic: 0 = binary64 definition, 1 = binary32 per element.
+int oracle_replica_spread(const void* x, int32_t x_is_bf16, int64_t stride, int32_t W,
+                          const int64_t* seg_off, const int64_t* seg_len, int32_t num_segments,
+                          int32_t arithmetic, double* out_std) {
+  if (!x || W < 1 || num_segments < 0 || !out_std) return 1;
+  const float* xf = static_cast<const float*>(x);
+  const uint16_t* xh = static_cast<const uint16_t*>(x);
+  if (arithmetic == 0) {
+    if (x_is_bf16)
+      replica_spread_impl<double>([xh](int64_t at) { return static_cast<double>(bf16_widen(xh[at])); },
+                                  stride, W, seg_off, seg_len, num_segments, out_std);
+    else
+      replica_spread_impl<double>([xf](int64_t at) { return static_cast<double>(xf[at]); },
+                                  stride, W, seg_off, seg_len, num_segments, out_std);
+  } else {
+    if (x_is_bf16)
+      replica_spread_impl<float>([xh](int64_t at) { return bf16_widen(xh[at]); },
+                                 stride, W, seg_off, seg_len, num_segments, out_std);
+    else
+      replica_spread_impl<float>([xf](int64_t at) { return xf[at]; },
+                                 stride, W, seg_off, seg_len, num_segments, out_std);
+  }
   return 0;
 }
 

@@ -71,6 +71,8 @@ def _load():
     L.noloco_outer_step.restype = C.c_int
     L.noloco_outer_step.argtypes = [C.c_void_p, C.POINTER(_Arena), C.POINTER(_HParams),
                                     C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
+    L.noloco_replica_spread.restype = C.c_int
+    L.noloco_replica_spread.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     L.noloco_copy_probe.restype = C.c_int
     L.noloco_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     L.noloco_read_probe.restype = C.c_int
@@ -86,7 +88,7 @@ _lib = _load()
 
 EXPORTS = ("noloco_plan_groups", "noloco_merge_segments", "noloco_launch_plan_create",
            "noloco_launch_plan_destroy", "noloco_launch_plan_info", "noloco_launch_plan_tune",
-           "noloco_outer_step", "noloco_copy_probe", "noloco_read_probe", "noloco_fill_probe",
+           "noloco_outer_step", "noloco_replica_spread", "noloco_copy_probe", "noloco_read_probe", "noloco_fill_probe",
            "noloco_strerror")
 
 
@@ -191,6 +193,12 @@ def outer_step(plan: LaunchPlan, phi, delta, theta, hparams, members, group_offs
     _check(_lib.noloco_outer_step(plan._handle, C.byref(arena), C.byref(hp), m.ctypes.data,
                                   o.ctypes.data, len(o) - 1, _stream(stream)),
            "noloco_outer_step")
+
+
+def replica_spread(plan: LaunchPlan, x, x_dtype: int, out_std, stream=None):
+    """noloco_replica_spread: out_std (device float64 [num_segments + 1]) <- pooled std across the W rows of x."""
+    _check(_lib.noloco_replica_spread(plan._handle, _ptr(x), int(x_dtype), _ptr(out_std), _stream(stream)),
+           "noloco_replica_spread")
 
 
 def copy_probe(dst, src, nbytes: int, stream=None):

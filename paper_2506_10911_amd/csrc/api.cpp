@@ -47,6 +47,13 @@ struct noloco_launch_plan {
   int64_t table_offset[3] = {0, 0, 0};       // entry index of each table inside dev_spans
   int64_t tiles[3] = {0, 0, 0};              // tiles per group for each tile size
   noloco::KernelChoice choice{-1, -1, -1, -1};   // -1 = chosen per launch, see resolve()
+  // replica-spread pass: per-tensor tiles (unmerged segments), their partial sums
+  int32_t num_segments = 0;                  // as given by the caller, empty ones included
+  int64_t seg_tiles_total = 0;
+  Span* dev_seg_spans = nullptr;             // points into dev_spans
+  noloco::SegmentTiles* dev_seg_tiles = nullptr;
+  double* dev_partials = nullptr;            // [seg_tiles_total + num_segments]
+  int32_t num_seg_spans = 0;
 };
 
 extern "C" noloco_status noloco_launch_plan_create(const noloco_arena* arena,
@@ -84,14 +91,53 @@ extern "C" noloco_status noloco_launch_plan_create(const noloco_arena* arena,
     plan->tiles[t] = noloco::build_spans(plan->runs, kTileSizes[t], &one);
     all.insert(all.end(), one.begin(), one.end());
   }
+  // Table for the replica-spread pass: one span per non-empty segment in the caller's order,
+  // 1024-column tiles, so that every tile lies inside one tensor.
+  plan->num_segments = arena->num_segments;
+  std::vector<noloco_segment> nonempty;
+  std::vector<noloco::SegmentTiles> seg_tiles(static_cast<size_t>(arena->num_segments));
+  for (int32_t i = 0; i < arena->num_segments; ++i)
+    if (arena->segments[i].numel > 0) nonempty.push_back(arena->segments[i]);
+  const int64_t seg_span_offset = static_cast<int64_t>(all.size());
+  plan->seg_tiles_total = noloco::build_spans(nonempty, kTileSizes[0], &one);
+  plan->num_seg_spans = static_cast<int32_t>(nonempty.size());
+  all.insert(all.end(), one.begin(), one.end());
+  for (int32_t i = 0, k = 0; i < arena->num_segments; ++i) {
+    noloco::SegmentTiles& st = seg_tiles[static_cast<size_t>(i)];
+    st.numel = arena->segments[i].numel;
+    if (st.numel > 0) {
+      st.first_tile = one[static_cast<size_t>(k)].tile_prefix;
+      st.num_tiles = one[static_cast<size_t>(k) + 1].tile_prefix - st.first_tile;
+      ++k;
+    } else {
+      st.first_tile = st.num_tiles = 0;
+    }
+  }
+  if (plan->seg_tiles_total > 0x7FFFFFFFll) {
+    delete plan;
+    return NOLOCO_ERR_UNSUPPORTED;
+  }
+
+  // One device allocation: span tables, per-segment tile ranges, partial sums.
+  const size_t spans_bytes = (all.size() * sizeof(Span) + 255) / 256 * 256;
+  const size_t segs_bytes = (seg_tiles.size() * sizeof(noloco::SegmentTiles) + 255) / 256 * 256;
+  const size_t partial_bytes =
+      static_cast<size_t>(plan->seg_tiles_total + plan->num_segments + 1) * sizeof(double);
+  char* block = nullptr;
   if (hipGetDevice(&plan->device) != hipSuccess ||
-      hipMalloc(reinterpret_cast<void**>(&plan->dev_spans), all.size() * sizeof(Span)) != hipSuccess) {
+      hipMalloc(reinterpret_cast<void**>(&block), spans_bytes + segs_bytes + partial_bytes) != hipSuccess) {
     delete plan;
     return NOLOCO_ERR_DEVICE;
   }
-  // Synchronous copy from pageable memory: the table is final when create returns.
-  if (hipMemcpy(plan->dev_spans, all.data(), all.size() * sizeof(Span), hipMemcpyHostToDevice) !=
-      hipSuccess) {
+  plan->dev_spans = reinterpret_cast<Span*>(block);
+  plan->dev_seg_spans = plan->dev_spans + seg_span_offset;
+  plan->dev_seg_tiles = reinterpret_cast<noloco::SegmentTiles*>(block + spans_bytes);
+  plan->dev_partials = reinterpret_cast<double*>(block + spans_bytes + segs_bytes);
+  // Synchronous copies from pageable memory: the tables are final when create returns.
+  if (hipMemcpy(plan->dev_spans, all.data(), all.size() * sizeof(Span), hipMemcpyHostToDevice) != hipSuccess ||
+      (!seg_tiles.empty() &&
+       hipMemcpy(plan->dev_seg_tiles, seg_tiles.data(), seg_tiles.size() * sizeof(noloco::SegmentTiles),
+                 hipMemcpyHostToDevice) != hipSuccess)) {
     (void)hipFree(plan->dev_spans);
     delete plan;
     return NOLOCO_ERR_DEVICE;
@@ -220,6 +266,30 @@ extern "C" noloco_status noloco_outer_step(const noloco_launch_plan* plan, const
     }
   }
   return NOLOCO_OK;
+}
+
+extern "C" noloco_status noloco_replica_spread(const noloco_launch_plan* plan, const void* x_device,
+                                               int32_t x_dtype, double* out_std_device,
+                                               void* hip_stream) {
+  if (plan == nullptr || x_device == nullptr || out_std_device == nullptr) return NOLOCO_ERR_NULL;
+  if (x_dtype != NOLOCO_F32 && x_dtype != NOLOCO_BF16) return NOLOCO_ERR_INVALID_ARG;
+  if (!aligned(x_device, NOLOCO_BASE_ALIGN_BYTES) || !aligned(out_std_device, 8))
+    return NOLOCO_ERR_ALIGNMENT;
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) return NOLOCO_ERR_DEVICE;
+  if (device != plan->device) return NOLOCO_ERR_INVALID_ARG;
+  noloco::SpreadArgs args;
+  args.x = x_device;
+  args.stride = plan->stride;
+  args.spans = plan->dev_seg_spans;
+  args.num_spans = plan->num_seg_spans;
+  args.W = plan->W;
+  args.inv_W = 1.0f / static_cast<float>(plan->W);
+  args.tiles = static_cast<uint32_t>(plan->seg_tiles_total);
+  args.partials = plan->dev_partials;
+  return noloco::launch_replica_spread(args, x_dtype, plan->dev_seg_tiles, plan->num_segments,
+                                       out_std_device, hip_stream) == 0
+             ? NOLOCO_OK : NOLOCO_ERR_DEVICE;
 }
 
 extern "C" noloco_status noloco_copy_probe(void* dst_device, const void* src_device, int64_t bytes,

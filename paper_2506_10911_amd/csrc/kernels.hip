@@ -451,6 +451,160 @@ __global__ void __launch_bounds__(kBlockThreads) fill_probe_kernel(f4* __restric
   }
 }
 
+// ---------------------------------------------------------------------------------------
+// Replica spread (results section of the paper: standard deviation of the weights across the
+// data-parallel replicas).  Read-only pass: per column the population variance over the W
+// rows in binary32 (sum in ascending row order, mean = sum * inv_W, then the squared
+// deviations summed in the same order, times inv_W), pooled in binary64 per tile in a fixed
+// order; two small kernels then pool tiles per tensor and tensors overall and take the roots.
+// ---------------------------------------------------------------------------------------
+
+__device__ __forceinline__ double wave_sum_fixed(double v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_down(v, off, 64);
+  return v;                                   // lane 0 holds the total
+}
+
+__device__ __forceinline__ double block_sum_fixed(double v, double* wave_part) {
+  const double w = wave_sum_fixed(v);
+  if ((threadIdx.x & 63) == 0) wave_part[threadIdx.x >> 6] = w;
+  __syncthreads();
+  return ((wave_part[0] + wave_part[1]) + wave_part[2]) + wave_part[3];   // same value in every thread
+}
+
+// Column variance of a lane's four columns from WT rows held in registers.
+template <int WT, typename Tag>
+__device__ __forceinline__ f4 column_variance_regs(const SpreadArgs& a, int64_t c) {
+  typedef ThetaMem<Tag, f4> TM;
+  typedef typename TM::elem TElem;
+  typedef typename TM::mem TMem;
+  const TElem* x = static_cast<const TElem*>(a.x);
+  f4 v[WT];
+#pragma unroll
+  for (int w = 0; w < WT; ++w)
+    v[w] = TM::widen(__builtin_nontemporal_load(reinterpret_cast<const TMem*>(x + w * a.stride + c)));
+  f4 sum = v[0];
+#pragma unroll
+  for (int w = 1; w < WT; ++w) sum = sum + v[w];
+  const f4 mean = sum * a.inv_W;
+  f4 q = (v[0] - mean) * (v[0] - mean);
+#pragma unroll
+  for (int w = 1; w < WT; ++w) {
+    const f4 dev = v[w] - mean;
+    q = q + dev * dev;
+  }
+  return q * a.inv_W;
+}
+
+// Any W: two sweeps over memory, four rows at a time.
+template <typename Tag>
+__device__ __forceinline__ f4 column_variance_mem(const SpreadArgs& a, int64_t c) {
+  typedef ThetaMem<Tag, f4> TM;
+  typedef typename TM::elem TElem;
+  typedef typename TM::mem TMem;
+  const TElem* x = static_cast<const TElem*>(a.x);
+  auto row = [&](int w) { return TM::widen(*reinterpret_cast<const TMem*>(x + w * a.stride + c)); };
+  f4 sum = row(0);
+  int w = 1;
+  for (; w + 4 <= a.W; w += 4) {
+    const f4 r0 = row(w), r1 = row(w + 1), r2 = row(w + 2), r3 = row(w + 3);
+    sum = sum + r0; sum = sum + r1; sum = sum + r2; sum = sum + r3;
+  }
+  for (; w < a.W; ++w) sum = sum + row(w);
+  const f4 mean = sum * a.inv_W;
+  const f4 d0 = row(0) - mean;
+  f4 q = d0 * d0;
+  w = 1;
+  for (; w + 4 <= a.W; w += 4) {
+    const f4 r0 = row(w) - mean, r1 = row(w + 1) - mean, r2 = row(w + 2) - mean, r3 = row(w + 3) - mean;
+    q = q + r0 * r0; q = q + r1 * r1; q = q + r2 * r2; q = q + r3 * r3;
+  }
+  for (; w < a.W; ++w) {
+    const f4 dev = row(w) - mean;
+    q = q + dev * dev;
+  }
+  return q * a.inv_W;
+}
+
+// WT = 0 selects the any-W routine.
+template <int WT, typename Tag>
+__global__ void __launch_bounds__(kBlockThreads) replica_spread_tiles(const SpreadArgs a) {
+  constexpr int kTile = kBlockThreads * kVecElems;
+  __shared__ double wave_part[kBlockThreads / 64];
+  const uint32_t tile = blockIdx.x;
+  int lo = 0, hi = a.num_spans;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.spans[mid].tile_prefix <= static_cast<int64_t>(tile)) lo = mid; else hi = mid;
+  }
+  const Span s = a.spans[lo];
+  const int64_t base = (s.first_block + (static_cast<int64_t>(tile) - s.tile_prefix)) * kTile;
+  const int64_t c0 = base > s.col_begin ? base : s.col_begin;
+  const int64_t c1 = base + kTile < s.col_end ? base + kTile : s.col_end;
+  const int64_t c = base + static_cast<int64_t>(threadIdx.x) * kVecElems;
+  double mine = 0.0;
+  if (c + kVecElems > c0 && c < c1) {         // the vector overlaps the tensor: load it whole, keep owned lanes
+    f4 var;
+    if constexpr (WT > 0) var = column_variance_regs<WT, Tag>(a, c);
+    else var = column_variance_mem<Tag>(a, c);
+    const float e0 = (c + 0 >= c0 && c + 0 < c1) ? var.x : 0.f;
+    const float e1 = (c + 1 >= c0 && c + 1 < c1) ? var.y : 0.f;
+    const float e2 = (c + 2 >= c0 && c + 2 < c1) ? var.z : 0.f;
+    const float e3 = (c + 3 >= c0 && c + 3 < c1) ? var.w : 0.f;
+    mine = ((static_cast<double>(e0) + static_cast<double>(e1)) + static_cast<double>(e2)) +
+           static_cast<double>(e3);
+  }
+  const double total = block_sum_fixed(mine, wave_part);
+  if (threadIdx.x == 0) a.partials[tile] = total;
+}
+
+// Workgroup s pools the tile sums of segment s (thread t takes tiles t, t+256, ...; then a fixed
+// tree) and writes that tensor's figure.
+__global__ void __launch_bounds__(kBlockThreads) replica_spread_segments(const double* partials,
+                                                                         const SegmentTiles* seg,
+                                                                         double* out_std, double* seg_sums) {
+  __shared__ double wave_part[kBlockThreads / 64];
+  const SegmentTiles st = seg[blockIdx.x];
+  double acc = 0.0;
+  for (int64_t t = threadIdx.x; t < st.num_tiles; t += kBlockThreads) acc += partials[st.first_tile + t];
+  const double total = block_sum_fixed(acc, wave_part);
+  if (threadIdx.x == 0) {
+    seg_sums[blockIdx.x] = total;
+    out_std[blockIdx.x] = st.numel > 0 ? sqrt(total / static_cast<double>(st.numel)) : 0.0;
+  }
+}
+
+// One workgroup pools the per-segment sums (same fixed scheme) for the overall figure.
+__global__ void __launch_bounds__(kBlockThreads) replica_spread_total(const SegmentTiles* seg,
+                                                                      int32_t num_segments,
+                                                                      const double* seg_sums, double* out_std) {
+  __shared__ double wave_part[kBlockThreads / 64];
+  __shared__ double count_part[kBlockThreads / 64];
+  double acc = 0.0, count = 0.0;            // element counts are below 2^53: exact in binary64
+  for (int s = threadIdx.x; s < num_segments; s += kBlockThreads) {
+    acc += seg_sums[s];
+    count += static_cast<double>(seg[s].numel);
+  }
+  const double total = block_sum_fixed(acc, wave_part);
+  const double n = block_sum_fixed(count, count_part);
+  if (threadIdx.x == 0) out_std[num_segments] = n > 0.0 ? sqrt(total / n) : 0.0;
+}
+
+template <typename Tag>
+hipError_t launch_spread_for_dtype(const SpreadArgs& a, hipStream_t s) {
+  const dim3 grid(a.tiles), block(kBlockThreads);
+  switch (a.W) {
+    case 2: hipLaunchKernelGGL((replica_spread_tiles<2, Tag>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((replica_spread_tiles<4, Tag>), grid, block, 0, s, a); break;
+    case 8: hipLaunchKernelGGL((replica_spread_tiles<8, Tag>), grid, block, 0, s, a); break;
+    case 16: hipLaunchKernelGGL((replica_spread_tiles<16, Tag>), grid, block, 0, s, a); break;
+    case 32: hipLaunchKernelGGL((replica_spread_tiles<32, Tag>), grid, block, 0, s, a); break;
+    case 64: hipLaunchKernelGGL((replica_spread_tiles<64, Tag>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((replica_spread_tiles<0, Tag>), grid, block, 0, s, a); break;
+  }
+  return hipGetLastError();
+}
+
 template <int N, typename Tag, int U>
 hipError_t launch_fixed_nt(const StepArgs& args, bool nt, dim3 grid, unsigned lds, hipStream_t s) {
   if (nt) hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, true>), grid, dim3(kBlockThreads), lds, s, args);
@@ -519,6 +673,23 @@ int launch_outer_step(const StepArgs& args, int32_t theta_dtype, const KernelCho
   const hipError_t e = theta_dtype == NOLOCO_BF16 ? launch_for_dtype<Bf16Tag>(args, choice, s)
                                                   : launch_for_dtype<float>(args, choice, s);
   return static_cast<int>(e);
+}
+
+int launch_replica_spread(const SpreadArgs& args, int32_t x_dtype, const SegmentTiles* seg_tiles,
+                          int32_t num_segments, double* out_std, void* stream) {
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (args.tiles > 0) {
+    const hipError_t e = x_dtype == NOLOCO_BF16 ? launch_spread_for_dtype<Bf16Tag>(args, s)
+                                                : launch_spread_for_dtype<float>(args, s);
+    if (e != hipSuccess) return static_cast<int>(e);
+  }
+  double* seg_sums = args.partials + args.tiles;   // per-segment sums are staged behind the tile partials
+  if (num_segments > 0)
+    hipLaunchKernelGGL(replica_spread_segments, dim3(static_cast<uint32_t>(num_segments)),
+                       dim3(kBlockThreads), 0, s, args.partials, seg_tiles, out_std, seg_sums);
+  hipLaunchKernelGGL(replica_spread_total, dim3(1), dim3(kBlockThreads), 0, s, seg_tiles, num_segments,
+                     seg_sums, out_std);
+  return static_cast<int>(hipGetLastError());
 }
 
 int launch_stream_probe(int mode, void* dst, const void* src, int64_t bytes, float value,

@@ -39,6 +39,26 @@ struct StepArgs {
   int32_t rows[NOLOCO_MAX_GROUP];  // group g = rows[g*n .. g*n+n), ascending worker ids
 };
 
+// Kernel arguments of the replica-spread pass (one tile = 1024 columns of ONE tensor).
+struct SpreadArgs {
+  const void* x;           // [W][stride] float or bf16
+  int64_t stride;
+  const Span* spans;       // one span per non-empty segment, caller's order, + sentinel
+  int32_t num_spans;
+  int32_t W;
+  float inv_W;
+  uint32_t tiles;
+  double* partials;        // [tiles] sum over the tile's owned columns of the per-column variance
+};
+
+// One entry per segment in the caller's order (empty ones included): where its tiles' partial
+// sums sit and how many elements it has.
+struct SegmentTiles {
+  int64_t first_tile;
+  int64_t num_tiles;
+  int64_t numel;
+};
+
 struct KernelChoice {
   int32_t vectors_per_thread;
   int32_t nontemporal;
@@ -61,6 +81,9 @@ int launch_outer_step(const StepArgs& args, int32_t theta_dtype, const KernelCho
                       void* stream);
 // mode 0 copy, 1 read only (dst = 4-byte sink), 2 fill
 int launch_stream_probe(int mode, void* dst, const void* src, int64_t bytes, float value, void* stream);
+
+int launch_replica_spread(const SpreadArgs& args, int32_t x_dtype, const SegmentTiles* seg_tiles,
+                          int32_t num_segments, double* out_std, void* stream);
 
 // tile size in elements for a kernel choice and group size
 int32_t tile_elems_for(int32_t n, int32_t vectors_per_thread);
