@@ -113,7 +113,7 @@ extern "C" noloco_status noloco_launch_plan_create(const noloco_arena* arena,
       st.first_tile = st.num_tiles = 0;
     }
   }
-  if (plan->seg_tiles_total > 0x7FFFFFFFll) {
+  if (plan->seg_tiles_total > 0x7FFF0000ll) {
     delete plan;
     return NOLOCO_ERR_UNSUPPORTED;
   }
@@ -287,6 +287,7 @@ extern "C" noloco_status noloco_replica_spread(const noloco_launch_plan* plan, c
   args.inv_W = 1.0f / static_cast<float>(plan->W);
   args.tiles = static_cast<uint32_t>(plan->seg_tiles_total);
   args.partials = plan->dev_partials;
+  args.xcd_map = plan->choice.xcd_map == 0 ? 0 : 1;   // automatic (-1) = contiguous per XCD
   return noloco::launch_replica_spread(args, x_dtype, plan->dev_seg_tiles, plan->num_segments,
                                        out_std_device, hip_stream) == 0
              ? NOLOCO_OK : NOLOCO_ERR_DEVICE;

@@ -531,7 +531,14 @@ template <int WT, typename Tag>
 __global__ void __launch_bounds__(kBlockThreads) replica_spread_tiles(const SpreadArgs a) {
   constexpr int kTile = kBlockThreads * kVecElems;
   __shared__ double wave_part[kBlockThreads / 64];
-  const uint32_t tile = blockIdx.x;
+  // Each XCD (workgroups are dealt to the 8 of them in turn) walks one contiguous eighth of the
+  // tiles, so that its consecutive 4 KiB row pieces spread over all 16 channels of its L2.
+  uint32_t tile = blockIdx.x;
+  if (a.xcd_map == 1) {
+    const uint32_t per_xcd = (a.tiles + kXcds - 1) / kXcds;
+    tile = (tile % kXcds) * per_xcd + tile / kXcds;
+    if (tile >= a.tiles) return;
+  }
   int lo = 0, hi = a.num_spans;
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
@@ -592,7 +599,7 @@ __global__ void __launch_bounds__(kBlockThreads) replica_spread_total(const Segm
 
 template <typename Tag>
 hipError_t launch_spread_for_dtype(const SpreadArgs& a, hipStream_t s) {
-  const dim3 grid(a.tiles), block(kBlockThreads);
+  const dim3 grid(a.xcd_map == 1 ? (a.tiles + kXcds - 1) / kXcds * kXcds : a.tiles), block(kBlockThreads);
   switch (a.W) {
     case 2: hipLaunchKernelGGL((replica_spread_tiles<2, Tag>), grid, block, 0, s, a); break;
     case 4: hipLaunchKernelGGL((replica_spread_tiles<4, Tag>), grid, block, 0, s, a); break;

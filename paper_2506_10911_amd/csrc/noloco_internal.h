@@ -48,6 +48,7 @@ struct SpreadArgs {
   int32_t W;
   float inv_W;
   uint32_t tiles;
+  int32_t xcd_map;         // 0 = workgroup i takes tile i, 1 = one contiguous eighth of the tiles per XCD
   double* partials;        // [tiles] sum over the tile's owned columns of the per-column variance
 };
 
