@@ -76,6 +76,31 @@ typedef enum noloco_dtype { NOLOCO_F32 = 0, NOLOCO_BF16 = 1 } noloco_dtype;
 noloco_status noloco_plan_groups(uint64_t seed, uint64_t step, int32_t W, int32_t n,
                                  int32_t* members, int32_t* group_offsets);
 
+/*
+ * Random pipeline routing plan (section "Inner optimizer step via dynamic pipeline routing";
+ * appendix algorithm "Random pipeline routing", its RandomRank): for one micro-batch of one
+ * step, and for every boundary b between pipeline stage b and stage b+1, a fresh uniformly
+ * random permutation pairs the W data-parallel replicas of stage b with those of stage b+1.
+ * Every replica sends to exactly one and receives from exactly one replica, so load is
+ * balanced, and the backward pass retraces the same path through recv_from.  Host only,
+ * integers only, a pure function of its arguments: every worker computes the same plan
+ * from the shared seed without communicating.
+ *
+ * Boundary b uses the subgroup planner's shuffle with a SplitMix64 stream started at
+ * mix64( mix64( mix64(seed ^ mix64(step + G)) ^ mix64(microbatch + 2G) ) ^ mix64(b + 3G) ),
+ * G = 0x9E3779B97F4A7C15.
+ *
+ *   num_stages   pipeline stages, >= 1 (one stage: nothing to route, nothing is written)
+ *   W            replicas per stage, >= 1
+ *   send_to      host, out, int32[(num_stages-1) * W]: send_to[b*W + r] = replica of stage
+ *                b+1 that replica r of stage b sends its outputs to
+ *   recv_from    host, out, int32[(num_stages-1) * W]: recv_from[b*W + q] = replica of stage b
+ *                that replica q of stage b+1 receives its inputs from (inverse of send_to)
+ */
+noloco_status noloco_plan_routes(uint64_t seed, uint64_t step, uint64_t microbatch,
+                                 int32_t num_stages, int32_t W, int32_t* send_to,
+                                 int32_t* recv_from);
+
 /* One tensor of the arena: `numel` consecutive elements starting `offset` elements into
  * every worker's row. */
 typedef struct noloco_segment {

@@ -42,6 +42,9 @@ def load(path):
         C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
         C.c_void_p, C.c_void_p, C.c_int32, C.c_double, C.c_double, C.c_double,
         C.c_void_p, C.c_void_p, C.c_int32]
+    L.oracle_plan_routes.restype = C.c_int
+    L.oracle_plan_routes.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_void_p]
     L.oracle_replica_spread.restype = C.c_int
     L.oracle_replica_spread.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int32, C.c_void_p,
                                         C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
@@ -76,6 +79,18 @@ def plan_groups(seed: int, step: int, W: int, n: int):
     if rc != 0:
         raise ValueError(f"no partition of {W} workers into groups of {n}")
     return members[:W], offsets
+
+
+def plan_routes(seed: int, step: int, microbatch: int, num_stages: int, W: int):
+    """Returns (send_to, recv_from), int32 [num_stages - 1, W] each; raises ValueError on bad sizes."""
+    b = max(num_stages - 1, 0)
+    send_to = np.full((b, max(W, 0)), -1, dtype=np.int32)
+    recv_from = np.full((b, max(W, 0)), -1, dtype=np.int32)
+    rc = lib().oracle_plan_routes(seed, step, microbatch, num_stages, W, send_to.ctypes.data,
+                                  recv_from.ctypes.data)
+    if rc != 0:
+        raise ValueError("bad routing sizes")
+    return send_to, recv_from
 
 
 def bf16_narrow(x) -> np.ndarray:

@@ -74,6 +74,7 @@ struct DrawStream {
   uint64_t base;
   uint64_t k = 0;
   DrawStream(uint64_t seed, uint64_t step) : base(mix64(seed ^ mix64(step + kGolden))) {}
+  explicit DrawStream(uint64_t raw_base) : base(raw_base) {}
   uint64_t next() {
     uint64_t r = mix64(base + (k + 1) * kGolden);
     ++k;
@@ -260,6 +261,37 @@ int oracle_plan_groups(uint64_t seed, uint64_t step, int32_t W, int32_t n,
     group_offsets[g] = g * n;
   }
   group_offsets[G] = W;
+  return 0;
+}
+
+// Random pipeline routing (section "Inner optimizer step via dynamic pipeline routing" and the
+// appendix algorithm "Random pipeline routing"): for every micro-batch of every step, and for
+// every boundary b between pipeline stage b and stage b+1, a fresh random permutation pairs the
+// W replicas of stage b with the W replicas of stage b+1, so every replica sends to exactly one
+// and receives from exactly one (balanced load), and the backward pass can retrace the path.
+//   send_to[b*W + r]   = replica of stage b+1 that replica r of stage b sends its outputs to
+//   recv_from[b*W + q] = replica of stage b that replica q of stage b+1 receives its inputs from
+// Every worker evaluates this from (seed, step, microbatch) alone; nothing is exchanged.
+// The draw stream of boundary b starts at
+//   mix64( mix64( mix64(seed ^ mix64(step + G)) ^ mix64(microbatch + 2G) ) ^ mix64(b + 3G) )
+// and drives the same top-down Fisher-Yates shuffle as the subgroup planner.
+int oracle_plan_routes(uint64_t seed, uint64_t step, uint64_t microbatch, int32_t num_stages,
+                       int32_t W, int32_t* send_to, int32_t* recv_from) {
+  if (num_stages < 1 || W < 1) return 1;
+  if (num_stages > 1 && (!send_to || !recv_from)) return 1;
+  const uint64_t step_key = mix64(seed ^ mix64(step + kGolden));
+  const uint64_t batch_key = mix64(step_key ^ mix64(microbatch + 2 * kGolden));
+  for (int32_t b = 0; b + 1 < num_stages; ++b) {
+    DrawStream s(mix64(batch_key ^ mix64(static_cast<uint64_t>(b) + 3 * kGolden)));
+    int32_t* to = send_to + static_cast<int64_t>(b) * W;
+    int32_t* from = recv_from + static_cast<int64_t>(b) * W;
+    for (int32_t r = 0; r < W; ++r) to[r] = r;
+    for (int32_t i = W - 1; i >= 1; --i) {
+      int32_t j = static_cast<int32_t>(s.bounded(static_cast<uint64_t>(i) + 1));
+      std::swap(to[i], to[j]);
+    }
+    for (int32_t r = 0; r < W; ++r) from[to[r]] = r;
+  }
   return 0;
 }
 

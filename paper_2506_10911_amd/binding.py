@@ -56,6 +56,9 @@ def _load():
     L = C.CDLL(_LIB_PATH)
     L.noloco_plan_groups.restype = C.c_int
     L.noloco_plan_groups.argtypes = [C.c_uint64, C.c_uint64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.noloco_plan_routes.restype = C.c_int
+    L.noloco_plan_routes.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_void_p]
     L.noloco_merge_segments.restype = C.c_int
     L.noloco_merge_segments.argtypes = [C.POINTER(_Segment), C.c_int32, C.c_int64,
                                         C.POINTER(_Segment), C.POINTER(C.c_int32)]
@@ -86,7 +89,7 @@ def _load():
 
 _lib = _load()
 
-EXPORTS = ("noloco_plan_groups", "noloco_merge_segments", "noloco_launch_plan_create",
+EXPORTS = ("noloco_plan_groups", "noloco_plan_routes", "noloco_merge_segments", "noloco_launch_plan_create",
            "noloco_launch_plan_destroy", "noloco_launch_plan_info", "noloco_launch_plan_tune",
            "noloco_outer_step", "noloco_replica_spread", "noloco_copy_probe", "noloco_read_probe", "noloco_fill_probe",
            "noloco_strerror")
@@ -133,6 +136,16 @@ def plan_groups(seed: int, step: int, W: int, n: int):
     _check(_lib.noloco_plan_groups(seed, step, W, n, members.ctypes.data, offsets.ctypes.data),
            "noloco_plan_groups")
     return members[:W], offsets
+
+
+def plan_routes(seed: int, step: int, microbatch: int, num_stages: int, W: int):
+    """noloco_plan_routes: (send_to, recv_from), int32 [num_stages - 1, W] each."""
+    b = max(int(num_stages) - 1, 0)
+    send_to = np.full((b, max(int(W), 0)), -1, dtype=np.int32)
+    recv_from = np.full((b, max(int(W), 0)), -1, dtype=np.int32)
+    _check(_lib.noloco_plan_routes(seed, step, microbatch, num_stages, W, send_to.ctypes.data,
+                                   recv_from.ctypes.data), "noloco_plan_routes")
+    return send_to, recv_from
 
 
 def merge_segments(segments, worker_stride: int):

@@ -73,6 +73,31 @@ def test_planner_errors():
     assert lib.noloco_plan_groups(0, 0, 4, 2, None, None) == 1
 
 
+def test_route_planner_matches_oracle_bit_for_bit():
+    rng = np.random.default_rng(321)
+    checked = 0
+    for stages in (1, 2, 3, 4, 8):
+        for W in (1, 2, 3, 8, 16, 64, 257):
+            for _ in range(12):
+                seed, step, mb = (int(rng.integers(0, 2**62)) for _ in range(3))
+                a = nl.plan_routes(seed, step, mb, stages, W)
+                b = oracle.plan_routes(seed, step, mb, stages, W)
+                assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+                checked += 1
+    for seed in range(10):
+        for step in range(20):
+            for mb in range(4):
+                a = nl.plan_routes(seed, step, mb, 4, 16)
+                b = oracle.plan_routes(seed, step, mb, 4, 16)
+                assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+                checked += 1
+    assert checked > 1000
+    for stages, W, status in [(0, 4, 2), (2, 0, 2)]:
+        with pytest.raises(nl.NolocoError) as e:
+            nl.plan_routes(0, 0, 0, stages, W)
+        assert e.value.status == status
+
+
 def test_merge_segments():
     assert nl.merge_segments([], 64) == []
     assert nl.merge_segments([(0, 64)], 64) == [(0, 64)]
