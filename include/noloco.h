@@ -241,6 +241,31 @@ noloco_status noloco_replica_spread(const noloco_launch_plan* plan, const void* 
                                     int32_t x_dtype, double* out_std_device, void* hip_stream);
 
 /*
+ * Latency model (section "Latency results", appendix "Latency analysis").  Host only, seeded
+ * Monte-Carlo; no GPU work.  Message and step times are LogNormal(mu, sigma^2), sigma >= 0.
+ *
+ * noloco_sim_tree_vs_pair: W workers (a power of two >= 2) at the leaves of a complete binary
+ * tree.  Reduce: a parent is ready when the later of its two children's messages has arrived
+ * (max(t1, t2), whose mean is (1 + erf(sigma/2)) exp(mu + sigma^2/2)); broadcast: the result
+ * travels back down one message per edge; the all-reduce ends when the last worker has it
+ * (2 t_c log2 W when sigma = 0).  Pairwise local averaging: two exchanges, each max(t1, t2).
+ *   out   host, double[4]: mean tree time, its standard error, mean pair time, its standard error
+ *
+ * noloco_sim_barrier_penalty: W workers run outer_steps rounds of inner_steps inner steps each
+ * (communication time ignored).  With a global barrier every round lasts as long as its slowest
+ * worker; with subgroup synchronisation a worker only waits for the n-1 partners
+ * noloco_plan_groups(seed, round, W, n) gives it.  Both clocks see the same step times.
+ *   out   host, double[2]: finishing time with the global barrier, finishing time (of the last
+ *         worker) with subgroup synchronisation
+ * Errors: NOLOCO_ERR_INVALID_ARG (sizes, sigma < 0, W not a power of two for the tree),
+ * NOLOCO_ERR_BAD_GROUPING (n does not divide W).
+ */
+noloco_status noloco_sim_tree_vs_pair(uint64_t seed, int32_t W, double mu, double sigma,
+                                      int32_t trials, double* out);
+noloco_status noloco_sim_barrier_penalty(uint64_t seed, int32_t W, int32_t n, int32_t inner_steps,
+                                         int32_t outer_steps, double mu, double sigma, double* out);
+
+/*
  * Measurement aids, not part of the method: plain streaming kernels over `bytes` bytes (a
  * multiple of 16; pointers 16-byte aligned) on `hip_stream`, with the same non-temporal
  * 16-byte accesses as the outer step.  Harnesses use them as yardsticks for what the chip's

@@ -59,6 +59,11 @@ def _load():
     L.noloco_plan_routes.restype = C.c_int
     L.noloco_plan_routes.argtypes = [C.c_uint64, C.c_uint64, C.c_uint64, C.c_int32, C.c_int32,
                                      C.c_void_p, C.c_void_p]
+    L.noloco_sim_tree_vs_pair.restype = C.c_int
+    L.noloco_sim_tree_vs_pair.argtypes = [C.c_uint64, C.c_int32, C.c_double, C.c_double, C.c_int32, C.c_void_p]
+    L.noloco_sim_barrier_penalty.restype = C.c_int
+    L.noloco_sim_barrier_penalty.argtypes = [C.c_uint64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                             C.c_double, C.c_double, C.c_void_p]
     L.noloco_merge_segments.restype = C.c_int
     L.noloco_merge_segments.argtypes = [C.POINTER(_Segment), C.c_int32, C.c_int64,
                                         C.POINTER(_Segment), C.POINTER(C.c_int32)]
@@ -91,7 +96,8 @@ _lib = _load()
 
 EXPORTS = ("noloco_plan_groups", "noloco_plan_routes", "noloco_merge_segments", "noloco_launch_plan_create",
            "noloco_launch_plan_destroy", "noloco_launch_plan_info", "noloco_launch_plan_tune",
-           "noloco_outer_step", "noloco_replica_spread", "noloco_copy_probe", "noloco_read_probe", "noloco_fill_probe",
+           "noloco_outer_step", "noloco_replica_spread", "noloco_sim_tree_vs_pair",
+           "noloco_sim_barrier_penalty", "noloco_copy_probe", "noloco_read_probe", "noloco_fill_probe",
            "noloco_strerror")
 
 
@@ -230,3 +236,19 @@ def fill_probe(dst, nbytes: int, value: float = 0.0, stream=None):
     """noloco_fill_probe: streams nbytes of `value` into dst (measurement aid)."""
     _check(_lib.noloco_fill_probe(_ptr(dst), int(nbytes), float(value), _stream(stream)),
            "noloco_fill_probe")
+
+
+def sim_tree_vs_pair(seed: int, W: int, mu: float, sigma: float, trials: int):
+    """noloco_sim_tree_vs_pair: dict with mean tree / pair times and their standard errors."""
+    out = np.zeros(4, dtype=np.float64)
+    _check(_lib.noloco_sim_tree_vs_pair(seed, W, mu, sigma, trials, out.ctypes.data),
+           "noloco_sim_tree_vs_pair")
+    return {"tree": out[0], "tree_se": out[1], "pair": out[2], "pair_se": out[3]}
+
+
+def sim_barrier_penalty(seed: int, W: int, n: int, inner_steps: int, outer_steps: int, mu: float, sigma: float):
+    """noloco_sim_barrier_penalty: (finishing time with a global barrier, with subgroup sync)."""
+    out = np.zeros(2, dtype=np.float64)
+    _check(_lib.noloco_sim_barrier_penalty(seed, W, n, inner_steps, outer_steps, mu, sigma,
+                                           out.ctypes.data), "noloco_sim_barrier_penalty")
+    return float(out[0]), float(out[1])

@@ -14,7 +14,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libnoloco.so")
-SOURCES = ["api.cpp", "planner.cpp", "launch_plan.cpp", "kernels.hip"]
+SOURCES = ["api.cpp", "planner.cpp", "launch_plan.cpp", "latency_model.cpp", "kernels.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
