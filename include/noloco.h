@@ -196,7 +196,8 @@ noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan, const noloco_tun
  *
  *   plan           from noloco_launch_plan_create for this layout
  *   arena          base pointers for this step; W, worker_stride and theta_dtype must match
- *                  the plan (arena->segments is not read again)
+ *                  the plan (arena->segments is not read again); the three arrays must not
+ *                  overlap (NOLOCO_ERR_INVALID_ARG)
  *   hparams        alpha, beta, gamma of Eq. 2
  *   members        host, int32[group_offsets[num_groups]]: worker ids, any order inside a group
  *   group_offsets  host, int32[num_groups + 1], group_offsets[0] = 0, non-decreasing;

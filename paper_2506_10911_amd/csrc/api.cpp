@@ -34,6 +34,12 @@ bool aligned(const void* p, uintptr_t bytes) {
   return (reinterpret_cast<uintptr_t>(p) % bytes) == 0;
 }
 
+// Do the byte ranges [a, a + a_bytes) and [b, b + b_bytes) share a byte?
+bool overlap(const void* a, uint64_t a_bytes, const void* b, uint64_t b_bytes) {
+  const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+  return a0 < b0 + b_bytes && b0 < a0 + a_bytes;
+}
+
 }  // namespace
 
 struct noloco_launch_plan {
@@ -92,14 +98,14 @@ extern "C" noloco_status noloco_launch_plan_create(const noloco_arena* arena,
     all.insert(all.end(), one.begin(), one.end());
   }
   // Table for the replica-spread pass: one span per non-empty segment in the caller's order,
-  // 1024-column tiles, so that every tile lies inside one tensor.
+  // cut into tiles of its own, so that every tile lies inside one tensor.
   plan->num_segments = arena->num_segments;
   std::vector<noloco_segment> nonempty;
   std::vector<noloco::SegmentTiles> seg_tiles(static_cast<size_t>(arena->num_segments));
   for (int32_t i = 0; i < arena->num_segments; ++i)
     if (arena->segments[i].numel > 0) nonempty.push_back(arena->segments[i]);
   const int64_t seg_span_offset = static_cast<int64_t>(all.size());
-  plan->seg_tiles_total = noloco::build_spans(nonempty, kTileSizes[0], &one);
+  plan->seg_tiles_total = noloco::build_spans(nonempty, noloco::spread_tile_elems_for(arena->W), &one);
   plan->num_seg_spans = static_cast<int32_t>(nonempty.size());
   all.insert(all.end(), one.begin(), one.end());
   for (int32_t i = 0, k = 0; i < arena->num_segments; ++i) {
@@ -195,6 +201,15 @@ extern "C" noloco_status noloco_outer_step(const noloco_launch_plan* plan, const
   if (!aligned(arena->phi, NOLOCO_BASE_ALIGN_BYTES) || !aligned(arena->delta, NOLOCO_BASE_ALIGN_BYTES) ||
       !aligned(arena->theta, NOLOCO_BASE_ALIGN_BYTES))
     return NOLOCO_ERR_ALIGNMENT;
+  {
+    // The step is in place and every array is both read and written: the three must be disjoint.
+    const uint64_t elems = static_cast<uint64_t>(plan->W) * static_cast<uint64_t>(plan->stride);
+    const uint64_t f32_bytes = elems * 4, theta_bytes = elems * (plan->theta_dtype == NOLOCO_BF16 ? 2 : 4);
+    if (overlap(arena->phi, f32_bytes, arena->delta, f32_bytes) ||
+        overlap(arena->phi, f32_bytes, arena->theta, theta_bytes) ||
+        overlap(arena->delta, f32_bytes, arena->theta, theta_bytes))
+      return NOLOCO_ERR_INVALID_ARG;
+  }
 
   // Validate the grouping completely before anything is launched.
   if (num_groups > 0 && group_offsets[0] != 0) return NOLOCO_ERR_BAD_GROUPING;

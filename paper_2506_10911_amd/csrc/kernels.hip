@@ -526,13 +526,13 @@ __device__ __forceinline__ f4 column_variance_mem(const SpreadArgs& a, int64_t c
   return q * a.inv_W;
 }
 
-// WT = 0 selects the any-W routine.
-template <int WT, typename Tag>
+// WT = 0 selects the any-W routine.  U = 16-byte vectors per thread: a tile is 1024*U columns.
+template <int WT, int U, typename Tag>
 __global__ void __launch_bounds__(kBlockThreads) replica_spread_tiles(const SpreadArgs a) {
-  constexpr int kTile = kBlockThreads * kVecElems;
+  constexpr int kTile = kBlockThreads * kVecElems * U;
   __shared__ double wave_part[kBlockThreads / 64];
   // Each XCD (workgroups are dealt to the 8 of them in turn) walks one contiguous eighth of the
-  // tiles, so that its consecutive 4 KiB row pieces spread over all 16 channels of its L2.
+  // tiles, so that its consecutive row pieces spread over all 16 channels of its L2.
   uint32_t tile = blockIdx.x;
   if (a.xcd_map == 1) {
     const uint32_t per_xcd = (a.tiles + kXcds - 1) / kXcds;
@@ -548,18 +548,34 @@ __global__ void __launch_bounds__(kBlockThreads) replica_spread_tiles(const Spre
   const int64_t base = (s.first_block + (static_cast<int64_t>(tile) - s.tile_prefix)) * kTile;
   const int64_t c0 = base > s.col_begin ? base : s.col_begin;
   const int64_t c1 = base + kTile < s.col_end ? base + kTile : s.col_end;
-  const int64_t c = base + static_cast<int64_t>(threadIdx.x) * kVecElems;
   double mine = 0.0;
-  if (c + kVecElems > c0 && c < c1) {         // the vector overlaps the tensor: load it whole, keep owned lanes
-    f4 var;
-    if constexpr (WT > 0) var = column_variance_regs<WT, Tag>(a, c);
-    else var = column_variance_mem<Tag>(a, c);
-    const float e0 = (c + 0 >= c0 && c + 0 < c1) ? var.x : 0.f;
-    const float e1 = (c + 1 >= c0 && c + 1 < c1) ? var.y : 0.f;
-    const float e2 = (c + 2 >= c0 && c + 2 < c1) ? var.z : 0.f;
-    const float e3 = (c + 3 >= c0 && c + 3 < c1) ? var.w : 0.f;
-    mine = ((static_cast<double>(e0) + static_cast<double>(e1)) + static_cast<double>(e2)) +
-           static_cast<double>(e3);
+  if (c0 == base && c1 == base + kTile) {     // whole tile: all U vectors' loads can be in flight together
+    f4 var[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t c = base + (u * kBlockThreads + static_cast<int64_t>(threadIdx.x)) * kVecElems;
+      if constexpr (WT > 0) var[u] = column_variance_regs<WT, Tag>(a, c);
+      else var[u] = column_variance_mem<Tag>(a, c);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      mine += ((static_cast<double>(var[u].x) + static_cast<double>(var[u].y)) +
+               static_cast<double>(var[u].z)) + static_cast<double>(var[u].w);
+  } else {
+    for (int u = 0; u < U; ++u) {
+      const int64_t c = base + (u * kBlockThreads + static_cast<int64_t>(threadIdx.x)) * kVecElems;
+      if (c + kVecElems > c0 && c < c1) {     // the vector overlaps the tensor: load it whole, keep owned lanes
+        f4 var;
+        if constexpr (WT > 0) var = column_variance_regs<WT, Tag>(a, c);
+        else var = column_variance_mem<Tag>(a, c);
+        const float e0 = (c + 0 >= c0 && c + 0 < c1) ? var.x : 0.f;
+        const float e1 = (c + 1 >= c0 && c + 1 < c1) ? var.y : 0.f;
+        const float e2 = (c + 2 >= c0 && c + 2 < c1) ? var.z : 0.f;
+        const float e3 = (c + 3 >= c0 && c + 3 < c1) ? var.w : 0.f;
+        mine += ((static_cast<double>(e0) + static_cast<double>(e1)) + static_cast<double>(e2)) +
+                static_cast<double>(e3);
+      }
+    }
   }
   const double total = block_sum_fixed(mine, wave_part);
   if (threadIdx.x == 0) a.partials[tile] = total;
@@ -600,14 +616,14 @@ __global__ void __launch_bounds__(kBlockThreads) replica_spread_total(const Segm
 template <typename Tag>
 hipError_t launch_spread_for_dtype(const SpreadArgs& a, hipStream_t s) {
   const dim3 grid(a.xcd_map == 1 ? (a.tiles + kXcds - 1) / kXcds * kXcds : a.tiles), block(kBlockThreads);
-  switch (a.W) {
-    case 2: hipLaunchKernelGGL((replica_spread_tiles<2, Tag>), grid, block, 0, s, a); break;
-    case 4: hipLaunchKernelGGL((replica_spread_tiles<4, Tag>), grid, block, 0, s, a); break;
-    case 8: hipLaunchKernelGGL((replica_spread_tiles<8, Tag>), grid, block, 0, s, a); break;
-    case 16: hipLaunchKernelGGL((replica_spread_tiles<16, Tag>), grid, block, 0, s, a); break;
-    case 32: hipLaunchKernelGGL((replica_spread_tiles<32, Tag>), grid, block, 0, s, a); break;
-    case 64: hipLaunchKernelGGL((replica_spread_tiles<64, Tag>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((replica_spread_tiles<0, Tag>), grid, block, 0, s, a); break;
+  switch (a.W) {   // vectors per thread as in spread_tile_elems_for()
+    case 2: hipLaunchKernelGGL((replica_spread_tiles<2, 4, Tag>), grid, block, 0, s, a); break;
+    case 4: hipLaunchKernelGGL((replica_spread_tiles<4, 4, Tag>), grid, block, 0, s, a); break;
+    case 8: hipLaunchKernelGGL((replica_spread_tiles<8, 4, Tag>), grid, block, 0, s, a); break;
+    case 16: hipLaunchKernelGGL((replica_spread_tiles<16, 1, Tag>), grid, block, 0, s, a); break;
+    case 32: hipLaunchKernelGGL((replica_spread_tiles<32, 1, Tag>), grid, block, 0, s, a); break;
+    case 64: hipLaunchKernelGGL((replica_spread_tiles<64, 1, Tag>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((replica_spread_tiles<0, 1, Tag>), grid, block, 0, s, a); break;
   }
   return hipGetLastError();
 }
@@ -661,6 +677,11 @@ hipError_t launch_for_dtype(const StepArgs& args, const KernelChoice& choice, hi
 }
 
 }  // namespace
+
+int32_t spread_tile_elems_for(int32_t W) {
+  const int32_t u = (W == 2 || W == 4 || W == 8) ? 4 : 1;   // W = 16 measured faster with 1 than with 2
+  return kBlockThreads * kVecElems * u;
+}
 
 bool has_fixed_kernel(int32_t n) { return n == 1 || n == 2 || n == 4 || n == 8 || n == 16; }
 

@@ -39,7 +39,7 @@ struct StepArgs {
   int32_t rows[NOLOCO_MAX_GROUP];  // group g = rows[g*n .. g*n+n), ascending worker ids
 };
 
-// Kernel arguments of the replica-spread pass (one tile = 1024 columns of ONE tensor).
+// Kernel arguments of the replica-spread pass (one tile = spread_tile_elems_for(W) columns of ONE tensor).
 struct SpreadArgs {
   const void* x;           // [W][stride] float or bf16
   int64_t stride;
@@ -88,6 +88,8 @@ int launch_replica_spread(const SpreadArgs& args, int32_t x_dtype, const Segment
 
 // tile size in elements for a kernel choice and group size
 int32_t tile_elems_for(int32_t n, int32_t vectors_per_thread);
+// tile size of the replica-spread pass for W rows
+int32_t spread_tile_elems_for(int32_t W);
 bool has_fixed_kernel(int32_t n);
 
 }  // namespace noloco

@@ -235,11 +235,17 @@ def test_error_paths_launch_nothing():
 
 def test_group_larger_than_limit_is_unsupported():
     W = 300
-    phi = torch.zeros((W, 64), device="cuda")
-    plan = nl.LaunchPlan(phi, phi, phi, 64, W, nl.F32, [(0, 64)])
+    phi, delta, theta = (torch.zeros((W, 64), device="cuda") for _ in range(3))
+    plan = nl.LaunchPlan(phi, delta, theta, 64, W, nl.F32, [(0, 64)])
     with pytest.raises(nl.NolocoError) as e:
-        nl.outer_step(plan, phi, phi, phi, (0.9, 0.7, 1.0), list(range(W)), [0, W])
+        nl.outer_step(plan, phi, delta, theta, (0.9, 0.7, 1.0), list(range(W)), [0, W])
     assert e.value.status == 7
+    # arrays that alias each other are refused: the step is in place on all three
+    for a, b, c in [(phi, phi, theta), (phi, delta, phi), (phi, delta, delta),
+                    (phi, phi.data_ptr() + 256, theta)]:
+        with pytest.raises(nl.NolocoError) as e:
+            nl.outer_step(plan, a, b, c, (0.9, 0.7, 1.0), [0, 1], [0, 2])
+        assert e.value.status == 2
 
 
 def test_resume_and_determinism():
