@@ -44,10 +44,11 @@ def test_small_arena_multi_step(theta_dtype, layout, n):
 
 @pytest.mark.parametrize("theta_dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("layout", ["tight", "gapped"])
-@pytest.mark.parametrize("n", [32, 64, 128, 5])
+@pytest.mark.parametrize("n", [32, 64, 128, 5, 256])
 def test_large_subgroups(theta_dtype, layout, n):
-    """W = 640: subgroups of 32 and 64 (phi kept in registers), 128 and 5 (two passes)."""
-    W = 640
+    """Subgroups of 32 and 64 (phi kept in registers), 128 and 5 (two passes), 256 (the largest
+    a call accepts), over W = 640 workers (768 for n = 256)."""
+    W = 768 if n == 256 else 640
     wl = workloads.make_small(theta_dtype=theta_dtype, W=W, n_schedule=(n,), layout=layout, count=8,
                               total=20_000, steps=2)
     case = SmallCase(wl, nl)

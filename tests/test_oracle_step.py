@@ -316,6 +316,42 @@ def test_first_step_from_common_start_is_identical_inside_a_group():
         np.testing.assert_array_equal(delta[a], delta[b])
 
 
+def run_noisy_quadratic(omega, steps=400, W=16, P=64, m=20, a=1.0, seed=0, hp=(0.5, 0.7, 1.0)):
+    """The setting of the paper's convergence theorem: loss 1/2 a (theta - c)^2 with c ~ N(0, 1) redrawn
+    every inner step, m inner SGD steps of rate omega from the slow weights, then one outer step over
+    random pairs. Returns the slow weights over the last half of the run, [steps/2, W, P]."""
+    rng = np.random.default_rng(seed)
+    phi = np.full((W, P), 3.0)                                   # common start, far from the optimum 0
+    delta = np.zeros((W, P))
+    tail = []
+    for t in range(steps):
+        theta = phi.copy()
+        for _ in range(m):
+            theta -= omega * a * (theta - rng.standard_normal((W, P)))
+        members, offsets = oracle.plan_groups(seed, t, W, 2)
+        oracle.outer_step_f64(phi, delta, theta, hp, members, offsets)
+        if t >= steps // 2:
+            tail.append(phi.copy())
+    return np.array(tail)
+
+
+def test_convergence_theorem_on_a_noisy_quadratic():
+    """Theorem of the paper: E(phi) -> 0 and V(phi) shrinks with the inner learning rate omega (the
+    theorem's leading-order statement is omega^2; at a finite number of inner steps the stationary
+    variance of this model lies between the omega and the omega^2 law) for hyper-parameters inside
+    the stability window (alpha = 0.5, beta = 0.7 > alpha, gamma = 1 lies in
+    sqrt(n/(2(n-1))) alpha = 0.5 < gamma < 1.5 for n = 2). A wrong sign in Eq. 1 would diverge here."""
+    big = run_noisy_quadratic(0.02)
+    small = run_noisy_quadratic(0.01)
+    for tail, omega in ((big, 0.02), (small, 0.01)):
+        assert np.isfinite(tail).all()
+        assert abs(tail.mean()) < 0.02                               # started at 3.0
+    ratio = big.var() / small.var()
+    assert 1.8 < ratio < 4.5, ratio                                  # omega halves -> variance falls 2x .. 4x
+    # replicas stay together: the spread across workers is of the order of the noise, not of the start
+    assert big.std(axis=1).mean() < 0.2
+
+
 # ---------------------------------------------------------------------------
 # binary32 instantiation: order invariance, agreement with binary64, segments
 # ---------------------------------------------------------------------------
