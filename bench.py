@@ -290,7 +290,8 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS, "traffic": recorded_traffic(wl.name),
-            "kernel": "outer_step_fixed" if n_of(args.warmup) in (1, 2, 4, 8, 16) else "outer_step_generic",
+            "kernel": ("outer_step_fixed" if n_of(args.warmup) in (1, 2, 4, 8, 16) else
+                       "outer_step_phi_resident" if n_of(args.warmup) in (32, 64) else "outer_step_generic"),
             "algorithmic_bytes_per_launch": alg_bytes,
             "bytes_per_update": wl.bytes_per_update,
             "avg_kernel_ms": avg_kernel_s * 1e3, "min_kernel_ms": min(kernel_ms), "max_kernel_ms": max(kernel_ms),
