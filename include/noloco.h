@@ -193,6 +193,9 @@ noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan, const noloco_tun
 /*
  * One outer step (Eq. 1-3 and the restart of the fast weights), fused, in place, enqueued
  * on `hip_stream` (a hipStream_t; null = the default stream).  Returns after the launch.
+ * The call allocates, copies and synchronises nothing on the device (the member table
+ * travels in the kernel arguments), so it may be recorded into a HIP graph by stream capture;
+ * the grouping is then fixed at capture time.
  *
  *   plan           from noloco_launch_plan_create for this layout
  *   arena          base pointers for this step; W, worker_stride and theta_dtype must match
