@@ -294,7 +294,8 @@ def main():
                        "outer_step_phi_resident" if n_of(args.warmup) in (32, 64) else "outer_step_generic"),
             "algorithmic_bytes_per_launch": alg_bytes,
             "bytes_per_update": wl.bytes_per_update,
-            "avg_kernel_ms": avg_kernel_s * 1e3, "min_kernel_ms": min(kernel_ms), "max_kernel_ms": max(kernel_ms),
+            "avg_kernel_ms": avg_kernel_s * 1e3, "median_kernel_ms": float(np.median(kernel_ms)),
+            "min_kernel_ms": min(kernel_ms), "max_kernel_ms": max(kernel_ms),
             "copy_probe_GBps": probes["copy"], "read_probe_GBps": probes["read"],
             "fill_probe_GBps": probes["fill"],
         },
