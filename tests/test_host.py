@@ -30,6 +30,21 @@ def test_library_exports_every_declared_symbol():
     assert set(nl.binding.EXPORTS) == set(names)
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 and as C++ on its own."""
+    import subprocess
+    src = tmp_path / "use.c"
+    src.write_text('#include "noloco.h"\n'
+                   'int probe(void) { noloco_hparams h = {0.9f, 0.7f, 1.0f}; noloco_segment s = {0, 4};\n'
+                   '  noloco_tuning t = {-1, -1, -1, -1}; (void)h; (void)s; (void)t;\n'
+                   '  return (int)sizeof(noloco_arena) + NOLOCO_MAX_GROUP + (int)NOLOCO_BF16; }\n')
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, "-c", str(src),
+                    "-o", str(tmp_path / "use_c.o")], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Werror", "-I", inc, "-x", "c++", "-c", str(src),
+                    "-o", str(tmp_path / "use_cpp.o")], check=True)
+
+
 def test_strerror_covers_all_codes():
     seen = {nl.strerror(c) for c in range(8)}
     assert len(seen) == 8 and "unknown status" not in seen
