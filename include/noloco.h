@@ -8,6 +8,11 @@
  *
  *   Eq. 1   Delta_j  = phi_j - theta_j                       (j in G; outer weights minus
  *                                                             local weights after the inner steps)
+ *           The paper prints Eq. 1 with the opposite sign and then subtracts the term in Eq. 2;
+ *           taken literally that moves phi away from theta.  The sign used here ("outer minus
+ *           local", DiLoCo's convention) is the one under which Eq. 2 descends, reduces to
+ *           DiLoCo's outer step when the subgroup is all workers, and reproduces the
+ *           contraction factor of the paper's own convergence analysis.
  *   Eq. 2   delta'_i = alpha*delta_i - (beta/n)*sum_j Delta_j
  *                      - gamma*(phi_i - (1/n)*sum_j phi_j)   (i in G, j over all of G, i included)
  *   Eq. 3   phi'_i   = phi_i + delta'_i
@@ -18,7 +23,8 @@
  * sums taken in ascending worker order.
  *
  * Conventions for every entry point
- *   - returns a noloco_status; never throws, never aborts, never prints;
+ *   - returns a noloco_status; never throws (no C++ exception crosses this boundary: a failed
+ *     host allocation comes back as NOLOCO_ERR_NO_MEMORY), never aborts, never prints;
  *   - all pointers are borrowed: the caller owns every host array and every device
  *     buffer; host arrays may be freed as soon as the call returns;
  *   - "device" pointers are HIP device memory of the GPU that is current when the
@@ -45,13 +51,16 @@ typedef enum noloco_status {
   NOLOCO_ERR_SEGMENT_OVERLAP = 4, /* two segments share an element, or a segment leaves the row */
   NOLOCO_ERR_ALIGNMENT = 5,       /* a base pointer or the worker stride is not aligned as required */
   NOLOCO_ERR_DEVICE = 6,          /* the HIP runtime reported an error */
-  NOLOCO_ERR_UNSUPPORTED = 7      /* a documented limit is exceeded (e.g. a group larger than NOLOCO_MAX_GROUP) */
+  NOLOCO_ERR_UNSUPPORTED = 7,     /* a documented limit is exceeded (e.g. a group larger than NOLOCO_MAX_GROUP) */
+  NOLOCO_ERR_NO_MEMORY = 8        /* a host-side allocation failed while building a plan or a simulation */
 } noloco_status;
 
 typedef enum noloco_dtype { NOLOCO_F32 = 0, NOLOCO_BF16 = 1 } noloco_dtype;
 
 /* Largest subgroup one call can handle (its member list travels in the kernel arguments). */
 #define NOLOCO_MAX_GROUP 256
+/* Largest number of worker rows a launch plan accepts (NOLOCO_ERR_UNSUPPORTED beyond it). */
+#define NOLOCO_MAX_WORKERS 65536
 /* Required alignment of phi/delta/theta base addresses, in bytes, and of worker_stride, in elements. */
 #define NOLOCO_BASE_ALIGN_BYTES 256
 #define NOLOCO_STRIDE_ALIGN_ELEMS 64
@@ -118,6 +127,10 @@ typedef struct noloco_segment {
  * NOLOCO_STRIDE_ALIGN_ELEMS; segment offsets and lengths are arbitrary (odd is fine).
  * Segments (host array) may come in any order, may leave gaps, must not overlap and
  * must end at or before worker_stride; empty segments are ignored.
+ * Speed note (results never depend on it): on MI355X the three arrays stream about 15 % faster
+ * when they lie in different 96 GiB thirds of the GPU's memory than when they are neighbours
+ * inside one third.  An arena that fills most of the memory is spread by itself; a small one
+ * gains from being allocated with two temporary spacer allocations in between.
  */
 typedef struct noloco_arena {
   float* phi;              /* device, in/out */
@@ -169,7 +182,8 @@ noloco_status noloco_launch_plan_info(const noloco_launch_plan* plan, int64_t* e
                                       int32_t* num_runs, int64_t* num_tiles, int32_t* tile_elems);
 
 /*
- * Launch-shape knobs.  Results never depend on them, only speed does.  Every field set to
+ * Launch-shape knobs: an aid for measurement harnesses, not part of the method's interface.
+ * Results never depend on them, only speed does.  Every field set to
  * -1 means "automatic": the library picks the measured best for MI355X per subgroup size
  * (the state of a new plan).  The call replaces all four fields.
  *   vectors_per_thread  16-byte vectors each thread handles per tile: 1, 2 or 4 (subgroups of
@@ -207,6 +221,12 @@ noloco_status noloco_launch_plan_tune(noloco_launch_plan* plan, const noloco_tun
  *                  group g is members[group_offsets[g] .. group_offsets[g+1])
  *   num_groups     >= 0
  *
+ * The call makes no heap allocation on the host either: the grouping is validated and bucketed
+ * by size in fixed stack storage.  Groups of each size go out in one kernel launch per
+ * NOLOCO_MAX_GROUP member rows (and per 2^32 threads of grid), sizes ascending.  Every argument
+ * and every limit is checked before the first launch; if the HIP runtime then refuses a launch
+ * (NOLOCO_ERR_DEVICE) earlier launches of the same call may already have updated their groups'
+ * rows, so after NOLOCO_ERR_DEVICE the arena's contents are undefined.
  * The groups must be disjoint and hold valid worker ids (NOLOCO_ERR_BAD_GROUPING
  * otherwise, nothing is launched).  They need not cover all workers: rows of workers in
  * no group are left untouched (a peer that dropped out of this round).  Groups may differ
@@ -270,7 +290,8 @@ noloco_status noloco_sim_barrier_penalty(uint64_t seed, int32_t W, int32_t n, in
                                          int32_t outer_steps, double mu, double sigma, double* out);
 
 /*
- * Measurement aids, not part of the method: plain streaming kernels over `bytes` bytes (a
+ * Measurement aids for harnesses, not part of the method and outside the interface the method
+ * needs (noloco_plan_groups, the launch plan, noloco_outer_step): plain streaming kernels over `bytes` bytes (a
  * multiple of 16; pointers 16-byte aligned) on `hip_stream`, with the same non-temporal
  * 16-byte accesses as the outer step.  Harnesses use them as yardsticks for what the chip's
  * HBM delivers to pure reads, pure writes and a 1:1 copy, and to calibrate the profiler's

@@ -203,15 +203,21 @@ class LaunchPlan:
             pass
 
 
+def _int32_address(values):
+    a = np.ascontiguousarray(values, dtype=np.int32)
+    return a, a.__array_interface__["data"][0]
+
+
 def outer_step(plan: LaunchPlan, phi, delta, theta, hparams, members, group_offsets, stream=None):
     """noloco_outer_step: one fused outer step in place, enqueued on `stream` (default: torch's current)."""
     arena = plan._arena(phi, delta, theta)
-    hp = _HParams(*[float(x) for x in hparams])
-    m = np.ascontiguousarray(members, dtype=np.int32)
-    o = np.ascontiguousarray(group_offsets, dtype=np.int32)
-    _check(_lib.noloco_outer_step(plan._handle, C.byref(arena), C.byref(hp), m.ctypes.data,
-                                  o.ctypes.data, len(o) - 1, _stream(stream)),
-           "noloco_outer_step")
+    hp = _HParams(float(hparams[0]), float(hparams[1]), float(hparams[2]))
+    m, m_at = _int32_address(members)
+    o, o_at = _int32_address(group_offsets)
+    status = _lib.noloco_outer_step(plan._handle, C.byref(arena), C.byref(hp), m_at, o_at, len(o) - 1,
+                                    _stream(stream))
+    if status != 0:
+        raise NolocoError(status, "noloco_outer_step")
 
 
 def replica_spread(plan: LaunchPlan, x, x_dtype: int, out_std, stream=None):

@@ -86,6 +86,16 @@ template <bool NT, typename T> __device__ __forceinline__ void st(T* p, T v) {
   else *p = v;
 }
 
+// Enqueue a kernel and return the launch status itself (hipLaunchKernel), so that an error some
+// earlier, unrelated call left behind on this thread is neither reported as ours nor cleared.
+template <typename T> struct same { typedef T type; };
+template <typename... KArgs>
+hipError_t enqueue(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t s,
+                   typename same<KArgs>::type... args) {
+  void* argv[] = {static_cast<void*>(&args)...};
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, 0, s);
+}
+
 // Which tile of which group this workgroup owns, and that tile's column range.
 struct TileRef {
   uint32_t group;
@@ -95,7 +105,7 @@ struct TileRef {
 };
 
 __device__ __forceinline__ bool locate_tile(const StepArgs& a, int tile_elems, TileRef& r) {
-  const uint32_t tiles = static_cast<uint32_t>(a.num_tiles);   // host guarantees tiles*groups < 2^31
+  const uint32_t tiles = static_cast<uint32_t>(a.num_tiles);   // host keeps tiles*groups below the grid limit
   // Workgroup -> work item.  The hardware deals consecutive workgroups to the 8 XCDs in turn,
   // and each XCD's L2 interleaves its 16 channels at 4 KiB; handing an XCD every 8th tile
   // would confine it to a few of its channels, so the map below gives each XCD runs of
@@ -113,22 +123,23 @@ __device__ __forceinline__ bool locate_tile(const StepArgs& a, int tile_elems, T
     }
     if (item >= a.work_items) return false;
   }
-  uint32_t tile;
+  uint32_t local;
   if (a.group_major) {
     r.group = item / tiles;
-    tile = item - r.group * tiles;
+    local = item - r.group * tiles;
   } else {
     const uint32_t groups = static_cast<uint32_t>(a.num_groups);
-    tile = item / groups;
-    r.group = item - tile * groups;
+    local = item / groups;
+    r.group = item - local * groups;
   }
+  const int64_t tile = a.tile_offset + static_cast<int64_t>(local);
   int lo = 0, hi = a.num_spans;             // spans[hi] is the sentinel: its prefix is the tile total
   while (hi - lo > 1) {
     const int mid = (lo + hi) >> 1;
-    if (a.spans[mid].tile_prefix <= static_cast<int64_t>(tile)) lo = mid; else hi = mid;
+    if (a.spans[mid].tile_prefix <= tile) lo = mid; else hi = mid;
   }
   const Span s = a.spans[lo];
-  r.base = (s.first_block + (static_cast<int64_t>(tile) - s.tile_prefix)) * tile_elems;
+  r.base = (s.first_block + (tile - s.tile_prefix)) * tile_elems;
   r.c0 = r.base > s.col_begin ? r.base : s.col_begin;
   const int64_t end = r.base + tile_elems;
   r.c1 = end < s.col_end ? end : s.col_end;
@@ -617,30 +628,29 @@ template <typename Tag>
 hipError_t launch_spread_for_dtype(const SpreadArgs& a, hipStream_t s) {
   const dim3 grid(a.xcd_map == 1 ? (a.tiles + kXcds - 1) / kXcds * kXcds : a.tiles), block(kBlockThreads);
   switch (a.W) {   // vectors per thread as in spread_tile_elems_for()
-    case 2: hipLaunchKernelGGL((replica_spread_tiles<2, 4, Tag>), grid, block, 0, s, a); break;
-    case 4: hipLaunchKernelGGL((replica_spread_tiles<4, 4, Tag>), grid, block, 0, s, a); break;
-    case 8: hipLaunchKernelGGL((replica_spread_tiles<8, 4, Tag>), grid, block, 0, s, a); break;
-    case 16: hipLaunchKernelGGL((replica_spread_tiles<16, 1, Tag>), grid, block, 0, s, a); break;
-    case 32: hipLaunchKernelGGL((replica_spread_tiles<32, 1, Tag>), grid, block, 0, s, a); break;
-    case 64: hipLaunchKernelGGL((replica_spread_tiles<64, 1, Tag>), grid, block, 0, s, a); break;
-    default: hipLaunchKernelGGL((replica_spread_tiles<0, 1, Tag>), grid, block, 0, s, a); break;
+    case 2: return enqueue(replica_spread_tiles<2, 4, Tag>, grid, block, s, a);
+    case 4: return enqueue(replica_spread_tiles<4, 4, Tag>, grid, block, s, a);
+    case 8: return enqueue(replica_spread_tiles<8, 4, Tag>, grid, block, s, a);
+    case 16: return enqueue(replica_spread_tiles<16, 1, Tag>, grid, block, s, a);
+    case 32: return enqueue(replica_spread_tiles<32, 1, Tag>, grid, block, s, a);
+    case 64: return enqueue(replica_spread_tiles<64, 1, Tag>, grid, block, s, a);
+    default: return enqueue(replica_spread_tiles<0, 1, Tag>, grid, block, s, a);
   }
-  return hipGetLastError();
 }
 
 template <int N, typename Tag, int U>
-hipError_t launch_fixed_nt(const StepArgs& args, bool nt, dim3 grid, unsigned lds, hipStream_t s) {
-  if (nt) hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, true>), grid, dim3(kBlockThreads), lds, s, args);
-  else    hipLaunchKernelGGL((outer_step_fixed<N, Tag, U, false>), grid, dim3(kBlockThreads), lds, s, args);
-  return hipGetLastError();
+hipError_t launch_fixed_nt(const StepArgs& args, bool nt, dim3 grid, hipStream_t s) {
+  const dim3 block(kBlockThreads);
+  return nt ? enqueue(outer_step_fixed<N, Tag, U, true>, grid, block, s, args)
+            : enqueue(outer_step_fixed<N, Tag, U, false>, grid, block, s, args);
 }
 
 template <int N, typename Tag>
-hipError_t launch_fixed(const StepArgs& args, int u, bool nt, dim3 grid, unsigned lds, hipStream_t s) {
+hipError_t launch_fixed(const StepArgs& args, int u, bool nt, dim3 grid, hipStream_t s) {
   constexpr int kMaxU = N <= 2 ? 4 : (N == 4 ? 2 : 1);
-  if constexpr (kMaxU >= 4) if (u == 4) return launch_fixed_nt<N, Tag, 4>(args, nt, grid, lds, s);
-  if constexpr (kMaxU >= 2) if (u == 2) return launch_fixed_nt<N, Tag, 2>(args, nt, grid, lds, s);
-  return launch_fixed_nt<N, Tag, 1>(args, nt, grid, lds, s);
+  if constexpr (kMaxU >= 4) if (u == 4) return launch_fixed_nt<N, Tag, 4>(args, nt, grid, s);
+  if constexpr (kMaxU >= 2) if (u == 2) return launch_fixed_nt<N, Tag, 2>(args, nt, grid, s);
+  return launch_fixed_nt<N, Tag, 1>(args, nt, grid, s);
 }
 
 template <typename Tag>
@@ -653,27 +663,23 @@ hipError_t launch_for_dtype(const StepArgs& args, const KernelChoice& choice, hi
     const uint32_t round = kXcds * static_cast<uint32_t>(args.xcd_map);
     wgs = (wgs + round - 1) / round * round;
   }
-  const dim3 grid(wgs);
-  const unsigned lds = 0;
+  const dim3 grid(wgs), block(kBlockThreads);
   switch (args.n) {
-    case 1: return launch_fixed<1, Tag>(args, u, nt, grid, lds, s);
-    case 2: return launch_fixed<2, Tag>(args, u, nt, grid, lds, s);
-    case 4: return launch_fixed<4, Tag>(args, u, nt, grid, lds, s);
-    case 8: return launch_fixed<8, Tag>(args, u, nt, grid, lds, s);
-    case 16: return launch_fixed<16, Tag>(args, u, nt, grid, lds, s);
+    case 1: return launch_fixed<1, Tag>(args, u, nt, grid, s);
+    case 2: return launch_fixed<2, Tag>(args, u, nt, grid, s);
+    case 4: return launch_fixed<4, Tag>(args, u, nt, grid, s);
+    case 8: return launch_fixed<8, Tag>(args, u, nt, grid, s);
+    case 16: return launch_fixed<16, Tag>(args, u, nt, grid, s);
     case 32:
-      if (nt) hipLaunchKernelGGL((outer_step_phi_resident<32, Tag, true>), grid, dim3(kBlockThreads), 0, s, args);
-      else    hipLaunchKernelGGL((outer_step_phi_resident<32, Tag, false>), grid, dim3(kBlockThreads), 0, s, args);
-      return hipGetLastError();
+      return nt ? enqueue(outer_step_phi_resident<32, Tag, true>, grid, block, s, args)
+                : enqueue(outer_step_phi_resident<32, Tag, false>, grid, block, s, args);
     case 64:
-      if (nt) hipLaunchKernelGGL((outer_step_phi_resident<64, Tag, true>), grid, dim3(kBlockThreads), 0, s, args);
-      else    hipLaunchKernelGGL((outer_step_phi_resident<64, Tag, false>), grid, dim3(kBlockThreads), 0, s, args);
-      return hipGetLastError();
+      return nt ? enqueue(outer_step_phi_resident<64, Tag, true>, grid, block, s, args)
+                : enqueue(outer_step_phi_resident<64, Tag, false>, grid, block, s, args);
     default: break;
   }
-  if (nt) hipLaunchKernelGGL((outer_step_generic<Tag, true>), grid, dim3(kBlockThreads), lds, s, args);
-  else    hipLaunchKernelGGL((outer_step_generic<Tag, false>), grid, dim3(kBlockThreads), lds, s, args);
-  return hipGetLastError();
+  return nt ? enqueue(outer_step_generic<Tag, true>, grid, block, s, args)
+            : enqueue(outer_step_generic<Tag, false>, grid, block, s, args);
 }
 
 }  // namespace
@@ -712,12 +718,14 @@ int launch_replica_spread(const SpreadArgs& args, int32_t x_dtype, const Segment
     if (e != hipSuccess) return static_cast<int>(e);
   }
   double* seg_sums = args.partials + args.tiles;   // per-segment sums are staged behind the tile partials
-  if (num_segments > 0)
-    hipLaunchKernelGGL(replica_spread_segments, dim3(static_cast<uint32_t>(num_segments)),
-                       dim3(kBlockThreads), 0, s, args.partials, seg_tiles, out_std, seg_sums);
-  hipLaunchKernelGGL(replica_spread_total, dim3(1), dim3(kBlockThreads), 0, s, seg_tiles, num_segments,
-                     seg_sums, out_std);
-  return static_cast<int>(hipGetLastError());
+  if (num_segments > 0) {
+    const hipError_t e = enqueue(replica_spread_segments, dim3(static_cast<uint32_t>(num_segments)),
+                                 dim3(kBlockThreads), s, static_cast<const double*>(args.partials),
+                                 seg_tiles, out_std, seg_sums);
+    if (e != hipSuccess) return static_cast<int>(e);
+  }
+  return static_cast<int>(enqueue(replica_spread_total, dim3(1), dim3(kBlockThreads), s, seg_tiles,
+                                  num_segments, static_cast<const double*>(seg_sums), out_std));
 }
 
 int launch_stream_probe(int mode, void* dst, const void* src, int64_t bytes, float value,
@@ -725,18 +733,16 @@ int launch_stream_probe(int mode, void* dst, const void* src, int64_t bytes, flo
   const int64_t vectors = bytes / 16;
   const int64_t per_block = kBlockThreads * 4;
   const int64_t blocks = (vectors + per_block - 1) / per_block;
-  if (blocks > 0x7FFFFFFFll) return static_cast<int>(hipErrorInvalidValue);
+  if (blocks > kMaxGridWorkgroups) return static_cast<int>(hipErrorInvalidValue);
   const dim3 grid(static_cast<uint32_t>(blocks)), block(kBlockThreads);
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (mode == 0)
-    hipLaunchKernelGGL(copy_probe_kernel, grid, block, 0, s, static_cast<f4*>(dst),
-                       static_cast<const f4*>(src), vectors);
-  else if (mode == 1)
-    hipLaunchKernelGGL(read_probe_kernel, grid, block, 0, s, static_cast<const f4*>(src), vectors,
-                       static_cast<float*>(dst));
-  else
-    hipLaunchKernelGGL(fill_probe_kernel, grid, block, 0, s, static_cast<f4*>(dst), vectors, value);
-  return static_cast<int>(hipGetLastError());
+    return static_cast<int>(enqueue(copy_probe_kernel, grid, block, s, static_cast<f4*>(dst),
+                                    static_cast<const f4*>(src), vectors));
+  if (mode == 1)
+    return static_cast<int>(enqueue(read_probe_kernel, grid, block, s, static_cast<const f4*>(src),
+                                    vectors, static_cast<float*>(dst)));
+  return static_cast<int>(enqueue(fill_probe_kernel, grid, block, s, static_cast<f4*>(dst), vectors, value));
 }
 
 }  // namespace noloco

@@ -8,6 +8,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <new>
 #include <vector>
 
 #include "noloco.h"
@@ -48,10 +49,8 @@ struct Moments {
   }
 };
 
-}  // namespace
-
-extern "C" noloco_status noloco_sim_tree_vs_pair(uint64_t seed, int32_t W, double mu, double sigma,
-                                                 int32_t trials, double* out) {
+noloco_status tree_vs_pair(uint64_t seed, int32_t W, double mu, double sigma, int32_t trials,
+                           double* out) {
   if (out == nullptr) return NOLOCO_ERR_NULL;
   if (W < 2 || (W & (W - 1)) != 0 || trials < 1 || !(sigma >= 0.0)) return NOLOCO_ERR_INVALID_ARG;
   Rng rng(seed, 0x74726565);
@@ -86,9 +85,8 @@ extern "C" noloco_status noloco_sim_tree_vs_pair(uint64_t seed, int32_t W, doubl
   return NOLOCO_OK;
 }
 
-extern "C" noloco_status noloco_sim_barrier_penalty(uint64_t seed, int32_t W, int32_t n,
-                                                    int32_t inner_steps, int32_t outer_steps,
-                                                    double mu, double sigma, double* out) {
+noloco_status barrier_penalty(uint64_t seed, int32_t W, int32_t n, int32_t inner_steps,
+                              int32_t outer_steps, double mu, double sigma, double* out) {
   if (out == nullptr) return NOLOCO_ERR_NULL;
   if (W < 1 || inner_steps < 1 || outer_steps < 1 || !(sigma >= 0.0)) return NOLOCO_ERR_INVALID_ARG;
   if (n < 1 || n > W || W % n != 0) return NOLOCO_ERR_BAD_GROUPING;
@@ -119,4 +117,28 @@ extern "C" noloco_status noloco_sim_barrier_penalty(uint64_t seed, int32_t W, in
   out[0] = barrier_clock;
   out[1] = *std::max_element(clock.begin(), clock.end());
   return NOLOCO_OK;
+}
+
+// Runs `body` and turns a failed host allocation into a status: no exception leaves the C ABI.
+template <typename Body> noloco_status guarded(Body body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return NOLOCO_ERR_NO_MEMORY;
+  } catch (...) {
+    return NOLOCO_ERR_INVALID_ARG;
+  }
+}
+
+}  // namespace
+
+extern "C" noloco_status noloco_sim_tree_vs_pair(uint64_t seed, int32_t W, double mu, double sigma,
+                                                 int32_t trials, double* out) {
+  return guarded([&] { return tree_vs_pair(seed, W, mu, sigma, trials, out); });
+}
+
+extern "C" noloco_status noloco_sim_barrier_penalty(uint64_t seed, int32_t W, int32_t n,
+                                                    int32_t inner_steps, int32_t outer_steps,
+                                                    double mu, double sigma, double* out) {
+  return guarded([&] { return barrier_penalty(seed, W, n, inner_steps, outer_steps, mu, sigma, out); });
 }

@@ -6,6 +6,7 @@
 // then cut at multiples of the tile size (in row coordinates, so interior tiles start on
 // 16-byte vector boundaries whatever the run's own start is).
 #include <algorithm>
+#include <new>
 
 #include "noloco_internal.h"
 
@@ -72,10 +73,16 @@ extern "C" noloco_status noloco_merge_segments(const noloco_segment* segments, i
                                                int32_t* num_runs) {
   if (num_runs == nullptr) return NOLOCO_ERR_NULL;
   *num_runs = 0;
-  std::vector<noloco_segment> runs;
-  noloco_status st = noloco::merge_segments(segments, num_segments, worker_stride, &runs);
-  if (st != NOLOCO_OK) return st;
-  *num_runs = static_cast<int32_t>(runs.size());
-  if (runs_out != nullptr) std::copy(runs.begin(), runs.end(), runs_out);
-  return NOLOCO_OK;
+  try {
+    std::vector<noloco_segment> runs;
+    noloco_status st = noloco::merge_segments(segments, num_segments, worker_stride, &runs);
+    if (st != NOLOCO_OK) return st;
+    *num_runs = static_cast<int32_t>(runs.size());
+    if (runs_out != nullptr) std::copy(runs.begin(), runs.end(), runs_out);
+    return NOLOCO_OK;
+  } catch (const std::bad_alloc&) {      // no exception leaves the C ABI
+    return NOLOCO_ERR_NO_MEMORY;
+  } catch (...) {
+    return NOLOCO_ERR_INVALID_ARG;
+  }
 }

@@ -30,7 +30,8 @@ struct StepArgs {
   const Span* spans;       // device, num_spans + 1 entries (last is a sentinel holding the tile total)
   int32_t num_spans;
   int32_t num_groups;      // groups in this launch
-  int64_t num_tiles;       // tiles per group
+  int64_t num_tiles;       // tiles per group taken by this launch
+  int64_t tile_offset;     // first of them: the launch covers tiles [tile_offset, tile_offset + num_tiles)
   float alpha, beta, gamma, inv_n;
   int32_t n;               // group size
   int32_t group_major;     // work item -> (tile, group) order
@@ -68,6 +69,11 @@ struct KernelChoice {
 };
 
 constexpr uint32_t kXcds = 8;        // MI355X: 8 accelerator dies, workgroups are dealt to them round-robin
+
+// The HIP runtime refuses a launch whose grid.x * block.x exceeds 2^32 - 1.  Launches are cut
+// (over groups and over tile ranges) so that a grid stays at or below this many workgroups;
+// the margin leaves room for the rounding the XCD maps add.
+constexpr int64_t kMaxGridWorkgroups = (0xFFFFFFFFll / kBlockThreads) - 8 * 4096;
 
 // host: segment table -> runs (sorted, merged); see noloco_merge_segments
 noloco_status merge_segments(const noloco_segment* segments, int32_t num_segments,

@@ -22,14 +22,34 @@ import paper_2506_10911_amd as nl
 nl.library_path()          # loads libnoloco.so now; a missing library is an error, not a skip
 
 CASES = [
-    # name, steps compared, strided sample size
-    ("tiny", 10, 1 << 20),          # the whole arena
-    ("gpt125m", 6, 1 << 18),
-    ("stage1p3b", 4, 1 << 18),
-    ("stage6p8b", 3, 1 << 18),
-    ("ragged_tight", 6, 1 << 16),   # n cycles 2, 4, 8
-    ("ragged_gapped", 6, 1 << 16),
+    # workload, W (0 = its own), subgroup size (0 = its schedule), steps compared, strided sample size,
+    # vectors per thread (-1 = the library's choice), elements sampled at each end of every tensor.
+    # The first six are the benchmark configurations with their own step counts.
+    ("tiny", 0, 0, 10, 1 << 20, -1, 64),          # the whole arena
+    ("gpt125m", 0, 0, 50, 1 << 18, -1, 64),
+    ("stage1p3b", 0, 0, 20, 1 << 18, -1, 64),
+    ("stage6p8b", 0, 0, 10, 1 << 18, -1, 64),
+    ("ragged_tight", 0, 0, 100, 1 << 16, -1, 16),   # n cycles 2, 4, 8
+    ("ragged_gapped", 0, 0, 100, 1 << 16, -1, 16),
+    ("ragged_gapped", 0, 0, 6, 1 << 16, -1, 64),    # the same with a wide sample at every tensor edge
+    # Larger subgroups, up to all workers in one group (the paragraph after Eq. 3: the update then is
+    # DiLoCo's), in the shapes the measurements quote: registers (4, 16), phi-resident (32, 64),
+    # two-pass (3, 12).
+    ("stage6p8b", 0, 4, 3, 1 << 18, -1, 64),
+    ("stage6p8b", 0, 16, 3, 1 << 18, -1, 64),
+    ("ragged_tight", 0, 32, 3, 1 << 16, -1, 64),
+    ("ragged_tight", 0, 64, 3, 1 << 16, -1, 64),
+    ("stage1p3b", 48, 3, 3, 1 << 17, -1, 64),
+    ("stage1p3b", 48, 12, 3, 1 << 17, -1, 64),
+    # 16 groups of one worker with 1024-column tiles: 25.2 M workgroups, more than one grid may hold,
+    # so the call goes out as two launches over tile ranges.
+    ("stage6p8b", 0, 1, 2, 1 << 18, 1, 64),
 ]
+
+
+def case_id(c):
+    return c[0] + (f"-W{c[1]}" if c[1] else "") + (f"-n{c[2]}" if c[2] else "") + (f"-vpt{c[5]}" if c[5] > 0 else "") + \
+        (f"-{c[3]}steps" if c[0] == "ragged_gapped" else "")
 
 
 def gap_columns(wl):
@@ -39,15 +59,19 @@ def gap_columns(wl):
     return np.flatnonzero(~inside)
 
 
-@pytest.mark.parametrize("name,steps,strided", CASES, ids=[c[0] for c in CASES])
-def test_full_size_sampled_parity(name, steps, strided):
+@pytest.mark.parametrize("name,workers,subgroup,steps,strided,vpt,edge", CASES, ids=[case_id(c) for c in CASES])
+def test_full_size_sampled_parity(name, workers, subgroup, steps, strided, vpt, edge):
     wl = workloads.make(name)
+    if workers:
+        wl.W = workers
     W, S = wl.W, wl.stride
+    torch.cuda.empty_cache()
     need = W * S * (8 + wl.theta_bytes) + (2 << 30)
     free, _ = torch.cuda.mem_get_info()
-    if need > free:
-        pytest.skip(f"{name}: needs {need / 1e9:.0f} GB, {free / 1e9:.0f} GB free")
-    print(f"[case] {name}: W={W} P={wl.P} tensors={len(wl.tensors)} theta={wl.theta_dtype}", flush=True)
+    # every configuration fits an MI355X by design (the largest takes 257.8 of 288 GiB): no skip
+    assert need <= free, f"{name}: needs {need / 1e9:.0f} GB, only {free / 1e9:.0f} GB free"
+    print(f"[case] {name}: W={W} n={subgroup or wl.n_schedule} P={wl.P} tensors={len(wl.tensors)} "
+          f"theta={wl.theta_dtype} steps={steps}", flush=True)
     dev = torch.device("cuda")
     tdt = torch.float32 if wl.theta_dtype == "f32" else torch.bfloat16
     phi = torch.empty((W, S), dtype=torch.float32, device=dev)
@@ -55,7 +79,7 @@ def test_full_size_sampled_parity(name, steps, strided):
     theta = torch.empty((W, S), dtype=tdt, device=dev)
     workloads.fill_phi0_device(phi, wl.seed, wl.init_std)
 
-    cols = workloads.column_sample(wl, strided)
+    cols = workloads.column_sample(wl, strided, edge)
     cols_t = torch.from_numpy(cols).to(dev)
     gaps = gap_columns(wl)
     gaps_t = torch.from_numpy(gaps).to(dev)
@@ -67,6 +91,7 @@ def test_full_size_sampled_parity(name, steps, strided):
     o_phi = phi[:, cols_t].cpu().numpy()
     o_delta = np.zeros_like(o_phi)
     plan = nl.LaunchPlan(phi, delta, theta, S, W, nl.F32 if wl.theta_dtype == "f32" else nl.BF16, wl.segments)
+    plan.tune(vectors_per_thread=vpt)
     info = plan.info()
     assert info["elements_per_worker"] == wl.P
     assert info["num_runs"] == (1 if name != "ragged_gapped" else len(wl.tensors))
@@ -78,7 +103,7 @@ def test_full_size_sampled_parity(name, steps, strided):
         theta[:, cols_t] = theta_to_device(np.ascontiguousarray(o_theta), dev)
         if len(gaps):
             theta[:, gaps_t] = float("nan")
-        n = wl.n_at(t)
+        n = subgroup or wl.n_at(t)
         members, offsets = nl.plan_groups(wl.seed, t, W, n)
         om, oo = oracle.plan_groups(wl.seed, t, W, n)
         assert members.tolist() == om.tolist() and offsets.tolist() == oo.tolist()

@@ -352,12 +352,19 @@ def test_probes():
 def test_tuning_is_validated_and_automatic_by_default():
     wl = workloads.make_small(W=8, layout="tight", count=4, total=3000)
     case = SmallCase(wl, nl, canary=False)
-    assert case.plan.info()["tile_elems"] == 4096              # automatic: 4 vectors per thread for pairs
+    # automatic: an arena too small to give every CU eight 4096-column tiles takes the smallest tile;
+    # a big one takes 4 vectors per thread for pairs (plans only describe a layout: no memory is touched)
+    assert case.plan.info()["tile_elems"] == 1024
+    big = nl.LaunchPlan(case.d_phi, case.d_delta, case.d_theta, 1 << 26, 8, nl.F32, [(0, 1 << 26)])
+    assert big.info()["tile_elems"] == 4096
+    big.destroy()
     for bad in [dict(vectors_per_thread=3), dict(nontemporal=2), dict(group_major=-2), dict(xcd_map=4097)]:
         with pytest.raises(nl.NolocoError) as e:
             case.plan.tune(**bad)
         assert e.value.status == 2
     case.plan.tune(vectors_per_thread=1)
     assert case.plan.info()["tile_elems"] == 1024
-    case.plan.tune()                                           # back to automatic
+    case.plan.tune(vectors_per_thread=4)
     assert case.plan.info()["tile_elems"] == 4096
+    case.plan.tune()                                           # back to automatic
+    assert case.plan.info()["tile_elems"] == 1024

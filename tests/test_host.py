@@ -46,8 +46,8 @@ def test_header_is_plain_c(tmp_path):
 
 
 def test_strerror_covers_all_codes():
-    seen = {nl.strerror(c) for c in range(8)}
-    assert len(seen) == 8 and "unknown status" not in seen
+    seen = {nl.strerror(c) for c in range(9)}
+    assert len(seen) == 9 and "unknown status" not in seen
     assert nl.strerror(99) == "unknown status"
 
 
