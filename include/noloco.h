@@ -265,6 +265,26 @@ noloco_status noloco_replica_spread(const noloco_launch_plan* plan, const void* 
                                     int32_t x_dtype, double* out_std_device, void* hip_stream);
 
 /*
+ * noloco_replica_spread for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels, same result bit
+ * for bit as noloco_replica_spread; the difference is where the per-tile and per-tensor partial
+ * sums are staged: not in the plan's own buffer but in one file-scope device array of the library,
+ * 16 MiB (2 097 152 doubles) per GPU, which every GPU the library runs on holds until the process
+ * ends.  The call performs no device or host allocation and no free, directly or through a
+ * library routine (the array's device address is looked up once per GPU, normally already at
+ * noloco_launch_plan_create, otherwise on the first call on that GPU).
+ *   Limit: the plan's spread tiles (arena elements / 1024 for W = 16, 32, 64 or any other W;
+ *   / 4096 for W = 2, 4, 8) plus num_segments plus one must not exceed 2 097 152, else
+ *   NOLOCO_ERR_UNSUPPORTED and nothing is launched.
+ *   All calls on one GPU share that GPU's array, whichever plan or stream they use: calls that
+ *   overlap in time on one GPU race with each other.  Every slot a call reads it has written
+ *   first, so what an earlier call left behind is harmless and nothing needs clearing.
+ */
+noloco_status noloco_replica_spread_noalloc(const noloco_launch_plan* plan, const void* x_device,
+                                            int32_t x_dtype, double* out_std_device,
+                                            void* hip_stream);
+
+/*
  * Latency model (section "Latency results", appendix "Latency analysis").  Host only, seeded
  * Monte-Carlo; no GPU work.  Message and step times are LogNormal(mu, sigma^2), sigma >= 0.
  *

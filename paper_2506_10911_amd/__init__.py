@@ -7,7 +7,7 @@ it libnoloco.so, is loaded on first use of any name below, so that
 fallback: if the library is missing, that first use raises.
 """
 _NAMES = ("BF16", "F32", "LaunchPlan", "NolocoError", "copy_probe", "fill_probe", "read_probe",
-          "library_path", "merge_segments", "outer_step", "plan_groups", "plan_routes", "replica_spread", "sim_tree_vs_pair", "sim_barrier_penalty", "strerror",
+          "library_path", "merge_segments", "outer_step", "plan_groups", "plan_routes", "replica_spread", "replica_spread_noalloc", "sim_tree_vs_pair", "sim_barrier_penalty", "strerror",
           "binding")
 
 

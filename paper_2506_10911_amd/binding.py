@@ -81,6 +81,8 @@ def _load():
                                     C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p]
     L.noloco_replica_spread.restype = C.c_int
     L.noloco_replica_spread.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
+    L.noloco_replica_spread_noalloc.restype = C.c_int
+    L.noloco_replica_spread_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     L.noloco_copy_probe.restype = C.c_int
     L.noloco_copy_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     L.noloco_read_probe.restype = C.c_int
@@ -96,7 +98,8 @@ _lib = _load()
 
 EXPORTS = ("noloco_plan_groups", "noloco_plan_routes", "noloco_merge_segments", "noloco_launch_plan_create",
            "noloco_launch_plan_destroy", "noloco_launch_plan_info", "noloco_launch_plan_tune",
-           "noloco_outer_step", "noloco_replica_spread", "noloco_sim_tree_vs_pair",
+           "noloco_outer_step", "noloco_replica_spread", "noloco_replica_spread_noalloc",
+           "noloco_sim_tree_vs_pair",
            "noloco_sim_barrier_penalty", "noloco_copy_probe", "noloco_read_probe", "noloco_fill_probe",
            "noloco_strerror")
 
@@ -224,6 +227,12 @@ def replica_spread(plan: LaunchPlan, x, x_dtype: int, out_std, stream=None):
     """noloco_replica_spread: out_std (device float64 [num_segments + 1]) <- pooled std across the W rows of x."""
     _check(_lib.noloco_replica_spread(plan._handle, _ptr(x), int(x_dtype), _ptr(out_std), _stream(stream)),
            "noloco_replica_spread")
+
+
+def replica_spread_noalloc(plan: LaunchPlan, x, x_dtype: int, out_std, stream=None):
+    """noloco_replica_spread_noalloc: the same pass staged in the library's static per-GPU array."""
+    _check(_lib.noloco_replica_spread_noalloc(plan._handle, _ptr(x), int(x_dtype), _ptr(out_std),
+                                              _stream(stream)), "noloco_replica_spread_noalloc")
 
 
 def copy_probe(dst, src, nbytes: int, stream=None):

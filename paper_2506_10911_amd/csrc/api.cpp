@@ -137,6 +137,10 @@ noloco_status create_plan(const noloco_arena* arena, noloco_launch_plan** out) {
        hipMemcpy(plan->dev_seg_tiles, seg_tiles.data(), seg_tiles.size() * sizeof(noloco::SegmentTiles),
                  hipMemcpyHostToDevice) != hipSuccess))
     return NOLOCO_ERR_DEVICE;
+  // Resolve this GPU's static scratch array now, at set-up, so that noloco_replica_spread_noalloc
+  // finds the address cached.  A failure here only matters to that entry point, which reports it.
+  double* unused = nullptr;
+  (void)noloco::static_spread_scratch(&unused);
   *out = plan.release();
   return NOLOCO_OK;
 }
@@ -381,6 +385,20 @@ extern "C" noloco_status noloco_replica_spread(const noloco_launch_plan* plan, c
   const noloco_status st = check_spread_args(plan, x_device, x_dtype, out_std_device);
   if (st != NOLOCO_OK) return st;
   return spread_into(plan, x_device, x_dtype, out_std_device, plan->dev_partials, hip_stream);
+}
+
+extern "C" noloco_status noloco_replica_spread_noalloc(const noloco_launch_plan* plan,
+                                                       const void* x_device, int32_t x_dtype,
+                                                       double* out_std_device, void* hip_stream) {
+  const noloco_status st = check_spread_args(plan, x_device, x_dtype, out_std_device);
+  if (st != NOLOCO_OK) return st;
+  // tile sums, then per-segment sums, then one spare slot: same staging as the plan's buffer
+  if (plan->seg_tiles_total + plan->num_segments + 1 > noloco::kSpreadScratchDoubles)
+    return NOLOCO_ERR_UNSUPPORTED;
+  double* scratch = nullptr;
+  if (noloco::static_spread_scratch(&scratch) != 0 || scratch == nullptr) return NOLOCO_ERR_DEVICE;
+  // Nothing has to start at zero: every slot that is read is written first by this call's kernels.
+  return spread_into(plan, x_device, x_dtype, out_std_device, scratch, hip_stream);
 }
 
 extern "C" noloco_status noloco_copy_probe(void* dst_device, const void* src_device, int64_t bytes,

@@ -23,6 +23,8 @@
 //   phi'_a = phi_a + delta'_a;  theta'_a = narrow(phi'_a)
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "noloco_internal.h"
 
 namespace noloco {
@@ -682,6 +684,15 @@ hipError_t launch_for_dtype(const StepArgs& args, const KernelChoice& choice, hi
             : enqueue(outer_step_generic<Tag, false>, grid, block, s, args);
 }
 
+// Scratch of noloco_replica_spread_noalloc: tile partial sums, then per-segment sums.  One copy
+// per GPU, allocated with the code object and kept until the process ends.  In host code this
+// name is only a handle for hipGetSymbolAddress; kernels receive the resolved device address.
+static __device__ __align__(256) double spread_scratch[kSpreadScratchDoubles];
+
+constexpr int kMaxDevices = 64;
+double* scratch_of_device[kMaxDevices];          // resolved addresses, filled on first use per device
+std::atomic<bool> scratch_known[kMaxDevices];
+
 }  // namespace
 
 int32_t spread_tile_elems_for(int32_t W) {
@@ -726,6 +737,25 @@ int launch_replica_spread(const SpreadArgs& args, int32_t x_dtype, const Segment
   }
   return static_cast<int>(enqueue(replica_spread_total, dim3(1), dim3(kBlockThreads), s, seg_tiles,
                                   num_segments, static_cast<const double*>(seg_sums), out_std));
+}
+
+int static_spread_scratch(double** out) {
+  int device = -1;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return static_cast<int>(e);
+  if (device < 0 || device >= kMaxDevices) return static_cast<int>(hipErrorInvalidDevice);
+  if (!scratch_known[device].load(std::memory_order_acquire)) {
+    // Every GPU holds its own copy of the array at its own address: resolve with that GPU current.
+    // Two threads racing here resolve the same address twice, which is harmless.
+    void* address = nullptr;
+    e = hipGetSymbolAddress(&address, HIP_SYMBOL(spread_scratch));
+    if (e != hipSuccess) return static_cast<int>(e);
+    if (address == nullptr) return static_cast<int>(hipErrorInvalidSymbol);
+    scratch_of_device[device] = static_cast<double*>(address);
+    scratch_known[device].store(true, std::memory_order_release);
+  }
+  *out = scratch_of_device[device];
+  return 0;
 }
 
 int launch_stream_probe(int mode, void* dst, const void* src, int64_t bytes, float value,

@@ -75,6 +75,10 @@ constexpr uint32_t kXcds = 8;        // MI355X: 8 accelerator dies, workgroups a
 // the margin leaves room for the rounding the XCD maps add.
 constexpr int64_t kMaxGridWorkgroups = (0xFFFFFFFFll / kBlockThreads) - 8 * 4096;
 
+// Capacity, in doubles, of the file-scope device array that noloco_replica_spread_noalloc uses
+// in place of the plan's own partial-sum buffer (16 MiB per GPU).
+constexpr int64_t kSpreadScratchDoubles = 2 * 1024 * 1024;
+
 // host: segment table -> runs (sorted, merged); see noloco_merge_segments
 noloco_status merge_segments(const noloco_segment* segments, int32_t num_segments,
                              int64_t worker_stride, std::vector<noloco_segment>* runs);
@@ -91,6 +95,10 @@ int launch_stream_probe(int mode, void* dst, const void* src, int64_t bytes, flo
 
 int launch_replica_spread(const SpreadArgs& args, int32_t x_dtype, const SegmentTiles* seg_tiles,
                           int32_t num_segments, double* out_std, void* stream);
+
+// kernels.hip: address of the current device's copy of the static scratch array (resolved once
+// per device and cached).  Returns hipError_t as int; performs no allocation of its own.
+int static_spread_scratch(double** out);
 
 // tile size in elements for a kernel choice and group size
 int32_t tile_elems_for(int32_t n, int32_t vectors_per_thread);
