@@ -66,6 +66,7 @@ def parse():
     ap.add_argument("--out", default=None)
     ap.add_argument("--command", action="append", default=[])
     ap.add_argument("--title", default="")
+    ap.add_argument("--bench-log", default=None, help="with --summarize kernel_stats: the profiled run's own output")
     return ap.parse_args()
 
 
@@ -132,6 +133,13 @@ def summarize(args):
             if is_ours(r["Name"]):
                 lines.append(f"avg_kernel_ms[{short_kernel_name(r['Name'])}]: {float(r['AverageNs']) / 1e6:.4f}")
         lines.append("(at::native kernels are the untimed fake inner phase between steps and the arena set-up)")
+        if args.bench_log:
+            line = [l for l in open(args.bench_log) if l.startswith("{")][0]
+            r = json.loads(line)["roofline"]
+            lines += ["", "bench.py's own figures in the same run (HIP events on the launch stream, the 10 timed steps):",
+                      f"  avg_kernel_ms {r['avg_kernel_ms']:.4f}  min {r['min_kernel_ms']:.4f}  max {r['max_kernel_ms']:.4f}",
+                      f"  algorithmic bytes per launch {r['algorithmic_bytes_per_launch']}  ->  {r['achieved']:.0f} GB/s = "
+                      f"{100 * r['frac']:.1f} % of the {r['peak']:.0f} GB/s HBM peak"]
     elif args.summarize == "hbm_traffic":
         rows = _counter_rows(args.src)
         per = {}                                   # (kernel, counter) -> values in KiB per dispatch
@@ -175,9 +183,21 @@ def summarize(args):
         lines.append("Counter values per dispatch (mean over the launches of each kernel; sums over all L2 channels / shader engines):")
         for k in kernels:
             lines.append(f"{k}   ({len(dur[k]) // max(len(counters), 1)} launches, {statistics.mean(dur[k]):.3f} ms each under the profiler)")
+            mean = {c: statistics.mean(per[(k, c)]) for c in counters if (k, c) in per}
             for c in counters:
-                if (k, c) in per:
-                    lines.append(f"    {c:<44}{statistics.mean(per[(k, c)]):>22.1f}")
+                if c in mean:
+                    lines.append(f"    {c:<44}{mean[c]:>22.1f}")
+            # derived figures (TCC = L2 channel, EA = its port towards the fabric and HBM)
+            if mean.get("TCC_EA0_RDREQ_sum"):
+                lines.append(f"    -> EA read latency  {mean['TCC_EA0_RDREQ_LEVEL_sum'] / mean['TCC_EA0_RDREQ_sum']:.0f} L2 cycles "
+                             f"(RDREQ_LEVEL / RDREQ)")
+            if mean.get("TCC_EA0_WRREQ_sum"):
+                lines.append(f"    -> EA write latency {mean['TCC_EA0_WRREQ_LEVEL_sum'] / mean['TCC_EA0_WRREQ_sum']:.0f} L2 cycles "
+                             f"(WRREQ_LEVEL / WRREQ)")
+            if mean.get("TCC_CYCLE_sum"):
+                for c in ("TCC_EA0_RDREQ_DRAM_CREDIT_STALL_sum", "TCC_EA0_WRREQ_DRAM_CREDIT_STALL_sum", "TCC_TAG_STALL_sum"):
+                    if c in mean:
+                        lines.append(f"    -> {c} / TCC_CYCLE_sum = {100 * mean[c] / mean['TCC_CYCLE_sum']:.1f} % of L2-channel cycles")
     text = "\n".join(head + lines) + "\n"
     with open(args.out, "w") as f:
         f.write(text)
@@ -274,26 +294,28 @@ class Arena:
         # On MI355X an in-place stream over three arrays runs about 15 % slower when the arrays are
         # neighbours inside one 96 GiB third of the memory than when they lie in different thirds
         # (measured; consistent with the three ranks of a 12-high HBM3E stack sitting at the top of
-        # the physical address). An arena that fills the memory is spread by itself. A small one is
-        # allocated with two spacers in between, which are freed again at once: physical placement
-        # stays, the address space in between is available to others.
-        spread = (placement == "spread" and (1 << 30) <= f32_bytes <= REGION_BYTES * 7 // 8
-                  and free > 2 * REGION_BYTES + theta_bytes + (6 << 30))
-        spacers = []
-        self.phi = torch.empty((W, S), dtype=torch.float32, device=dev)
+        # the physical address). An arena that fills the memory is spread by itself. For a small one
+        # the harness takes one slab of 2 x 96 GiB + theta and carves phi, delta and theta out of it
+        # 96 GiB apart, so that element k of the three arrays always lies in three different thirds.
+        slab_bytes = 2 * REGION_BYTES + theta_bytes
+        spread = (placement == "spread" and need_delta and need_theta and (1 << 30) <= f32_bytes <= REGION_BYTES
+                  and free > slab_bytes + (6 << 30))
+        self.slab = None
         if spread:
-            spacers.append(torch.empty(REGION_BYTES - f32_bytes, dtype=torch.uint8, device=dev))
-        self.delta = torch.zeros((W, S), dtype=torch.float32, device=dev) if need_delta else None
-        if spread:
-            spacers.append(torch.empty(REGION_BYTES - f32_bytes, dtype=torch.uint8, device=dev))
-        self.theta = torch.empty((W, S), dtype=tdt, device=dev) if need_theta else None
-        del spacers
-        torch.cuda.empty_cache()
+            self.slab = torch.empty(slab_bytes, dtype=torch.uint8, device=dev)
+            self.phi = self.slab[:f32_bytes].view(torch.float32).view(W, S)
+            self.delta = self.slab[REGION_BYTES:REGION_BYTES + f32_bytes].view(torch.float32).view(W, S)
+            self.delta.zero_()
+            self.theta = self.slab[2 * REGION_BYTES:2 * REGION_BYTES + theta_bytes].view(tdt).view(W, S)
+        else:
+            self.phi = torch.empty((W, S), dtype=torch.float32, device=dev)
+            self.delta = torch.zeros((W, S), dtype=torch.float32, device=dev) if need_delta else None
+            self.theta = torch.empty((W, S), dtype=tdt, device=dev) if need_theta else None
         self.placement = "spread" if spread else "plain"
         self.resident_bytes = 2 * f32_bytes + theta_bytes
 
     def free(self, torch):
-        self.phi = self.delta = self.theta = None
+        self.phi = self.delta = self.theta = self.slab = None
         torch.cuda.empty_cache()
 
 
@@ -395,6 +417,26 @@ def graph_replay_us(torch, nl, wl, arena, plan, steps=20, replays=5):
     return best
 
 
+def eager_step_us(torch, nl, wl, arena, plan, steps=300):
+    """Host-clock cost of an eager step without the event records of the timed loop: plan + launch +
+    synchronize per step, and plan + launch back to back with one synchronize at the end."""
+    hp = (wl.alpha, wl.beta, wl.gamma)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(steps):
+        members, offsets = nl.plan_groups(wl.seed, t, wl.W, wl.n_at(t))
+        nl.outer_step(plan, arena.phi, arena.delta, arena.theta, hp, members, offsets)
+        torch.cuda.synchronize()
+    synced = (time.perf_counter() - t0) / steps * 1e6
+    t0 = time.perf_counter()
+    for t in range(steps):
+        members, offsets = nl.plan_groups(wl.seed, t, wl.W, wl.n_at(t))
+        nl.outer_step(plan, arena.phi, arena.delta, arena.theta, hp, members, offsets)
+    torch.cuda.synchronize()
+    streamed = (time.perf_counter() - t0) / steps * 1e6
+    return {"eager_us_per_step_synchronized": synced, "eager_us_per_step_back_to_back": streamed}
+
+
 def extra_outer(torch, nl, workloads, dev, name, placement, steps, warmup, subgroup=0):
     """A few steps of one configuration for the 'extra' section."""
     wl = workloads.make(name)
@@ -406,8 +448,10 @@ def extra_outer(torch, nl, workloads, dev, name, placement, steps, warmup, subgr
     run = run_outer_steps(torch, nl, workloads, wl, arena, plan, n_of, steps, warmup)
     res = extra_entry(wl, run, arena.placement, arena.resident_bytes)
     if name == "tiny":
+        res.update(eager_step_us(torch, nl, wl, arena, plan))
         res["graph_replay_us_per_step"] = graph_replay_us(torch, nl, wl, arena, plan)
-        res["note"] = "cache-resident (50 MB) and launch-bound: not an HBM measurement"
+        res["note"] = ("cache-resident (50 MB) and launch-bound: not an HBM measurement; the kernel itself runs "
+                       "18 us (rocprofv3), HIP events around so short a launch mostly time the launch")
     plan.destroy()
     arena.free(torch)
     return res

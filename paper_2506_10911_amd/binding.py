@@ -175,13 +175,25 @@ class LaunchPlan:
         self.worker_stride, self.W, self.theta_dtype = int(worker_stride), int(W), int(theta_dtype)
         self._segments = _segment_array(segments)
         self._num_segments = len(segments)
+        self._arena_key, self._arena_struct = None, None
+        self._hp_key, self._hp_struct = None, None
         arena = self._arena(phi, delta, theta)
         _check(_lib.noloco_launch_plan_create(C.byref(arena), C.byref(self._handle)),
                "noloco_launch_plan_create")
 
     def _arena(self, phi, delta, theta):
-        return _Arena(_ptr(phi), _ptr(delta), _ptr(theta), self.worker_stride, self.W,
-                      self.theta_dtype, self._segments, self._num_segments)
+        key = (_ptr(phi), _ptr(delta), _ptr(theta))
+        if key != self._arena_key:          # the struct of the last base pointers is kept: no per-step rebuild
+            self._arena_struct = _Arena(*key, self.worker_stride, self.W, self.theta_dtype,
+                                        self._segments, self._num_segments)
+            self._arena_key = key
+        return self._arena_struct
+
+    def _hparams(self, hparams):
+        key = (float(hparams[0]), float(hparams[1]), float(hparams[2]))
+        if key != self._hp_key:
+            self._hp_struct, self._hp_key = _HParams(*key), key
+        return self._hp_struct
 
     def info(self):
         e, r, t, te = C.c_int64(), C.c_int32(), C.c_int64(), C.c_int32()
@@ -214,7 +226,7 @@ def _int32_address(values):
 def outer_step(plan: LaunchPlan, phi, delta, theta, hparams, members, group_offsets, stream=None):
     """noloco_outer_step: one fused outer step in place, enqueued on `stream` (default: torch's current)."""
     arena = plan._arena(phi, delta, theta)
-    hp = _HParams(float(hparams[0]), float(hparams[1]), float(hparams[2]))
+    hp = plan._hparams(hparams)
     m, m_at = _int32_address(members)
     o, o_at = _int32_address(group_offsets)
     status = _lib.noloco_outer_step(plan._handle, C.byref(arena), C.byref(hp), m_at, o_at, len(o) - 1,
