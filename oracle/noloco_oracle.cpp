@@ -21,8 +21,10 @@
 //   restart of the fast weights theta'_i = phi'_i   (convergence appendix:
 //          the inner iteration of the next round starts from the slow weights)
 //   subgroup sampling           a fresh random permutation of the workers every
-//          outer step, cut into consecutive groups of n ("assign workers to
-//          groups via random permutations").  The paper names no generator;
+//          outer step, cut into consecutive groups of n (section "Inner
+//          optimizer step via dynamic pipeline routing" says groups come from
+//          random permutations; section "Outer optimizer step ..." that they
+//          are drawn afresh every iteration).  The paper names no generator;
 //          the one below is this build's own choice, stated in full here.
 //
 // Pins (tests/test_oracle_*.py, run without a GPU): hand-worked dyadic
@@ -31,7 +33,12 @@
 // tiny worker sets, the group-mean / global-mean / spread identities that
 // follow from Eq. 2-3, order invariance, the published SplitMix64
 // known-answer vector, partition validity and uniformity of the planner,
-// and an exhaustive 16-bit analogue of the bounded draw.
+// an exhaustive 16-bit analogue of the bounded draw, and planted mistakes in
+// the step and in both planners that those pins must catch.
+// Parity unpinned: the choice of generator and seed-mixing rule of the two
+// planners (the paper fixes only that the draws are uniform and fresh), and
+// the tree all-reduce time of the latency model for more than two workers
+// with sigma > 0 (oracle/latency.py).
 //
 // Build: g++ -O2 -std=c++17 -ffp-contract=off -shared -fPIC (see build.py).
 // -ffp-contract=off matters: the float instantiation is the bit-level target

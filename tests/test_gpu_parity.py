@@ -207,7 +207,7 @@ def test_error_paths_launch_nothing():
     # fills the arena from its plan)
     from paper_2506_10911_amd import binding as B
     for field, value in [("W", 4), ("worker_stride", wl.stride + 64), ("theta_dtype", nl.BF16)]:
-        arena = case.plan._arena(case.d_phi, case.d_delta, case.d_theta)
+        arena = B._Arena.from_buffer_copy(case.plan._arena(case.d_phi, case.d_delta, case.d_theta))
         setattr(arena, field, value)
         m = np.array(ok_m, dtype=np.int32)
         o = np.array(ok_o, dtype=np.int32)
