@@ -1,6 +1,6 @@
 // C ABI of the NoLoCo outer step: argument checking, the launch plan, and the split of one
 // outer step into kernel launches.  All arithmetic of the method is in kernels.hip.
-#include <hip/hip_runtime.h>
+#include <hip/hip_runtime_api.h>
 
 #include <algorithm>
 #include <cstdint>

@@ -695,22 +695,6 @@ std::atomic<bool> scratch_known[kMaxDevices];
 
 }  // namespace
 
-int32_t spread_tile_elems_for(int32_t W) {
-  const int32_t u = (W == 2 || W == 4 || W == 8) ? 4 : 1;   // W = 16 measured faster with 1 than with 2
-  return kBlockThreads * kVecElems * u;
-}
-
-bool has_fixed_kernel(int32_t n) { return n == 1 || n == 2 || n == 4 || n == 8 || n == 16; }
-
-int32_t tile_elems_for(int32_t n, int32_t vectors_per_thread) {
-  int32_t u = 1;
-  if (has_fixed_kernel(n)) {
-    const int32_t max_u = n <= 2 ? 4 : (n == 4 ? 2 : 1);
-    u = vectors_per_thread < max_u ? vectors_per_thread : max_u;
-  }
-  return kBlockThreads * kVecElems * u;
-}
-
 int launch_outer_step(const StepArgs& args, int32_t theta_dtype, const KernelChoice& choice,
                       void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);

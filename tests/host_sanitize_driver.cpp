@@ -1,11 +1,43 @@
-// Host-only exercise of the library's pure host code and of the oracle under AddressSanitizer and
-// UBSan (built and run by tests/test_host_sanitized.py; no GPU, no HIP runtime).
+// Host-only exercise of the library's host code and of the oracle under AddressSanitizer and
+// UBSan (built and run by tests/test_host_sanitized.py; no GPU, no HIP runtime).  The C ABI's
+// argument checking and launch splitting (api.cpp) run against stand-ins for the few HIP runtime
+// calls they make and for the kernel launchers of kernels.hip, which record what would be launched.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <vector>
 
 #include "noloco.h"
+#include "noloco_internal.h"
+
+// ---- stand-ins: device memory is host memory, launches are recorded ----
+extern "C" hipError_t hipGetDevice(int* device) { *device = 0; return hipSuccess; }
+extern "C" hipError_t hipMalloc(void** ptr, size_t size) {
+  *ptr = std::malloc(size ? size : 1);
+  return *ptr ? hipSuccess : hipErrorOutOfMemory;
+}
+extern "C" hipError_t hipFree(void* ptr) { std::free(ptr); return hipSuccess; }
+extern "C" hipError_t hipMemcpy(void* dst, const void* src, size_t size, hipMemcpyKind) {
+  std::memcpy(dst, src, size);
+  return hipSuccess;
+}
+namespace noloco {
+struct Launch { StepArgs args; KernelChoice choice; };
+static std::vector<Launch> launches;
+static int fail_at_launch = -1;              // index of the launch the stand-in refuses
+int launch_outer_step(const StepArgs& args, int32_t, const KernelChoice& choice, void*) {
+  if (static_cast<int>(launches.size()) == fail_at_launch) return 1;
+  launches.push_back(Launch{args, choice});
+  return 0;
+}
+int launch_replica_spread(const SpreadArgs&, int32_t, const SegmentTiles*, int32_t, double*, void*) { return 0; }
+int launch_stream_probe(int, void*, const void*, int64_t, float, void*) { return 0; }
+int static_spread_scratch(double** out) { static double slot[4]; *out = slot; return 0; }
+}  // namespace noloco
 
 extern "C" {
 int oracle_plan_groups(uint64_t, uint64_t, int32_t, int32_t, int32_t*, int32_t*);
@@ -77,6 +109,110 @@ int main() {
     double out[4];
     CHECK(oracle_replica_spread(phi.data(), 0, S, W, off, len, 3, 0, out) == 0);
     CHECK(oracle_replica_spread(theta16.data(), 1, S, W, off, len, 3, 1, out) == 0);
+  }
+  // ---- the C ABI's host path: validation, bucketing by group size, launch splitting ----
+  {
+    using noloco::launches;
+    float* const phi = reinterpret_cast<float*>(1ull << 40);       // never dereferenced on this path
+    float* const delta = reinterpret_cast<float*>(2ull << 40);
+    void* const theta = reinterpret_cast<void*>(3ull << 40);
+    const noloco_hparams hp = {0.9f, 0.7f, 1.0f};
+    auto make_plan = [&](int32_t W, int64_t stride, noloco_launch_plan** plan, noloco_arena* arena) {
+      static noloco_segment seg;
+      seg = noloco_segment{0, stride};
+      *arena = noloco_arena{phi, delta, theta, stride, W, NOLOCO_F32, &seg, 1};
+      return noloco_launch_plan_create(arena, plan);
+    };
+    noloco_launch_plan* plan = nullptr;
+    noloco_arena arena;
+    // (1) mixed group sizes, members unsorted, a worker left out, an empty group
+    CHECK(make_plan(9, 1 << 24, &plan, &arena) == NOLOCO_OK);
+    {
+      const int32_t members[8] = {7, 2, 5, 0, 3, 1, 8, 6}, offsets[5] = {0, 2, 2, 6, 8};
+      launches.clear();
+      CHECK(noloco_outer_step(plan, &arena, &hp, members, offsets, 4, nullptr) == NOLOCO_OK);
+      CHECK(launches.size() == 2);
+      const noloco::StepArgs& a = launches[0].args;            // sizes ascending: the pairs first
+      CHECK(a.n == 2 && a.num_groups == 2 && a.inv_n == 0.5f && a.tile_offset == 0);
+      CHECK(a.rows[0] == 2 && a.rows[1] == 7 && a.rows[2] == 6 && a.rows[3] == 8);
+      CHECK(a.num_tiles == (1 << 24) / 4096 && a.work_items == 2u * a.num_tiles);
+      CHECK(launches[0].choice.vectors_per_thread == 4 && a.group_major == 1 && a.xcd_map == 0);
+      const noloco::StepArgs& b = launches[1].args;
+      CHECK(b.n == 4 && b.num_groups == 1 && b.inv_n == 0.25f);
+      CHECK(b.rows[0] == 0 && b.rows[1] == 1 && b.rows[2] == 3 && b.rows[3] == 5);
+      CHECK(b.num_tiles == (1 << 24) / 2048 && b.group_major == 0 && b.xcd_map == 1);
+      // refused groupings launch nothing
+      const int32_t dup[4] = {0, 1, 1, 2}, two[3] = {0, 2, 4}, range[4] = {0, 1, 2, 9};
+      const int32_t bad_start[3] = {1, 2, 4}, decreasing[3] = {0, 3, 2};
+      launches.clear();
+      CHECK(noloco_outer_step(plan, &arena, &hp, dup, two, 2, nullptr) == NOLOCO_ERR_BAD_GROUPING);
+      CHECK(noloco_outer_step(plan, &arena, &hp, range, two, 2, nullptr) == NOLOCO_ERR_BAD_GROUPING);
+      CHECK(noloco_outer_step(plan, &arena, &hp, members, bad_start, 2, nullptr) == NOLOCO_ERR_BAD_GROUPING);
+      CHECK(noloco_outer_step(plan, &arena, &hp, members, decreasing, 2, nullptr) == NOLOCO_ERR_BAD_GROUPING);
+      CHECK(noloco_outer_step(plan, &arena, &hp, nullptr, two, 2, nullptr) == NOLOCO_ERR_NULL);
+      noloco_arena other = arena;
+      other.delta = phi + 64;                                  // aligned, but overlaps phi
+      CHECK(noloco_outer_step(plan, &other, &hp, members, offsets, 4, nullptr) == NOLOCO_ERR_INVALID_ARG);
+      CHECK(launches.empty());
+      CHECK(noloco_outer_step(plan, &arena, &hp, nullptr, nullptr, 0, nullptr) == NOLOCO_OK && launches.empty());
+      // the runtime refusing the second launch is reported
+      noloco::fail_at_launch = 1;
+      CHECK(noloco_outer_step(plan, &arena, &hp, members, offsets, 4, nullptr) == NOLOCO_ERR_DEVICE);
+      CHECK(launches.size() == 1);
+      noloco::fail_at_launch = -1;
+    }
+    CHECK(noloco_launch_plan_destroy(plan) == NOLOCO_OK);
+    // (2) more groups than one member table holds: 300 pairs go out as 128 + 128 + 44; a group of
+    //     257 is refused before anything is launched
+    CHECK(make_plan(600, 1 << 20, &plan, &arena) == NOLOCO_OK);
+    {
+      std::vector<int32_t> members(600), offsets(301);
+      for (int32_t w = 0; w < 600; ++w) members[w] = 599 - w;
+      for (int32_t g = 0; g <= 300; ++g) offsets[g] = 2 * g;
+      launches.clear();
+      CHECK(noloco_outer_step(plan, &arena, &hp, members.data(), offsets.data(), 300, nullptr) == NOLOCO_OK);
+      CHECK(launches.size() == 3 && launches[0].args.num_groups == 128 && launches[1].args.num_groups == 128 &&
+            launches[2].args.num_groups == 44);
+      CHECK(launches[2].args.rows[0] == 86 && launches[2].args.rows[1] == 87);   // group 256 = workers {87, 86}
+      std::vector<int32_t> big_offsets = {0, 2, 259, 261};
+      launches.clear();
+      CHECK(noloco_outer_step(plan, &arena, &hp, members.data(), big_offsets.data(), 3, nullptr) == NOLOCO_ERR_UNSUPPORTED);
+      CHECK(launches.empty());
+    }
+    CHECK(noloco_launch_plan_destroy(plan) == NOLOCO_OK);
+    // (3) more workgroups than one grid holds: the launch is cut over tile ranges that tile the row
+    CHECK(make_plan(2, 1ll << 35, &plan, &arena) == NOLOCO_OK);
+    {
+      const int32_t members[2] = {1, 0}, offsets[3] = {0, 1, 2};
+      for (int32_t vpt : {-1, 1}) {
+        const noloco_tuning tuning = {vpt, -1, -1, -1};
+        CHECK(noloco_launch_plan_tune(plan, &tuning) == NOLOCO_OK);
+        launches.clear();
+        CHECK(noloco_outer_step(plan, &arena, &hp, members, offsets, 2, nullptr) == NOLOCO_OK);
+        const int64_t tiles = (1ll << 35) / (vpt == 1 ? 1024 : 4096);
+        CHECK(launches.size() == (vpt == 1 ? 5u : 2u));
+        int64_t next = 0;
+        for (const noloco::Launch& l : launches) {
+          CHECK(l.args.n == 1 && l.args.num_groups == 2 && l.args.tile_offset == next);
+          CHECK(l.args.work_items == static_cast<uint64_t>(l.args.num_tiles) * 2);
+          CHECK(static_cast<int64_t>(l.args.work_items) <= noloco::kMaxGridWorkgroups);
+          next += l.args.num_tiles;
+        }
+        CHECK(next == tiles);
+      }
+    }
+    CHECK(noloco_launch_plan_destroy(plan) == NOLOCO_OK);
+    // (4) a small arena takes small tiles; limits of plan creation
+    CHECK(make_plan(4, 1 << 20, &plan, &arena) == NOLOCO_OK);
+    {
+      const int32_t members[4] = {0, 1, 2, 3}, offsets[3] = {0, 2, 4};
+      launches.clear();
+      CHECK(noloco_outer_step(plan, &arena, &hp, members, offsets, 2, nullptr) == NOLOCO_OK);
+      CHECK(launches.size() == 1 && launches[0].choice.vectors_per_thread == 1 && launches[0].args.num_tiles == 1024);
+    }
+    CHECK(noloco_launch_plan_destroy(plan) == NOLOCO_OK);
+    CHECK(make_plan(NOLOCO_MAX_WORKERS + 1, 64, &plan, &arena) == NOLOCO_ERR_UNSUPPORTED && plan == nullptr);
+    CHECK(make_plan(4, 63, &plan, &arena) == NOLOCO_ERR_ALIGNMENT);
   }
   std::printf("host sanitize driver: ok\n");
   return 0;
