@@ -37,7 +37,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 DEFAULT_WORKLOAD = "stage6p8b"  # the configuration the target is quoted on (fits one GPU: 257.8 GB)
 WORKLOADS = ["tiny", "gpt125m", "stage1p3b", "stage6p8b", "ragged_tight", "ragged_gapped"]
-REGION_BYTES = 96 << 30         # the GPU's memory behaves as three such regions, see alloc_arena()
+REGION_BYTES = 96 << 30         # the GPU's memory behaves as three such regions, see class Arena
 
 
 def parse():
