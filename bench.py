@@ -373,7 +373,7 @@ def per_n_figures(wl, run):
 def stream_probes(torch, nl, delta, W, S, dev):
     """Plain streaming kernels over the momentum array (its contents are no longer needed)."""
     half = (W // 2) * S * 4 // 16 * 16
-    probes = {"copy": None, "read": None, "fill": None}
+    probes = {"copy": None, "read": None, "fill": None, "runtime_copy": None}
     if half < (1 << 20):
         return probes
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
@@ -391,6 +391,19 @@ def stream_probes(torch, nl, delta, W, S, dev):
         c1.record()
         torch.cuda.synchronize()
         probes[name] = 3 * nbytes / (c0.elapsed_time(c1) / 1e3) / 1e9
+    # the HIP runtime's own device-to-device copy of the same bytes (torch's copy_ of a contiguous
+    # tensor is a hipMemcpyAsync): a yardstick that owes nothing to this library's kernels
+    flat = delta.view(-1)
+    n = half // 4
+    dst, src = flat[n:2 * n], flat[:n]
+    dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(3):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    probes["runtime_copy"] = 3 * 2 * half / (c0.elapsed_time(c1) / 1e3) / 1e9
     return probes
 
 
@@ -617,7 +630,7 @@ def main():
             "min_kernel_ms": min(kernel_ms), "max_kernel_ms": max(kernel_ms),
             "per_n": per_n_figures(wl, run),
             "copy_probe_GBps": probes["copy"], "read_probe_GBps": probes["read"],
-            "fill_probe_GBps": probes["fill"],
+            "fill_probe_GBps": probes["fill"], "runtime_copy_GBps": probes["runtime_copy"],
         },
         "host": {"plan_groups_us": float(np.median(run["plan_us"])),
                  "outer_step_call_us": float(np.median(run["call_us"])),

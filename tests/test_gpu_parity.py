@@ -296,6 +296,44 @@ def test_stream_argument_is_honoured():
     case.check("side stream")
 
 
+def test_one_plan_serves_two_threads_on_two_streams():
+    """A launch plan is immutable and the step keeps its scratch on the caller's stack, so two host
+    threads may step disjoint sets of workers through ONE plan at the same time, each on its own
+    stream. 40 steps per thread with changing pairings; the oracle applies the same steps one
+    thread after the other (the sets are disjoint, so the interleaving cannot matter)."""
+    import threading
+    wl = workloads.make_small(theta_dtype="bf16", W=8, layout="gapped")
+    case = SmallCase(wl, nl)
+    case.inner_phase(0)
+    hp = (wl.alpha, wl.beta, wl.gamma)
+    halves = ([0, 1, 2, 3], [4, 5, 6, 7])
+    rng = np.random.default_rng(5)
+    plans = [[rng.permutation(h).tolist() for _ in range(40)] for h in halves]
+    errors = []
+    torch.cuda.synchronize()
+
+    def work(steps):
+        try:
+            stream = torch.cuda.Stream()
+            for members in steps:
+                nl.outer_step(case.plan, case.d_phi, case.d_delta, case.d_theta, hp, members, [0, 2, 4], stream=stream)
+            stream.synchronize()
+        except Exception as e:            # reported by the main thread
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(p,)) for p in plans]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    torch.cuda.synchronize()
+    for steps in plans:
+        for members in steps:
+            oracle.outer_step_f32(case.phi, case.delta, case.theta, hp, members, [0, 2, 4], segments=wl.segments)
+    case.check("two threads, one plan")
+
+
 def test_outer_steps_replay_from_a_hip_graph():
     """noloco_outer_step allocates, copies and synchronises nothing, so a window of outer steps can
     be captured into a HIP graph (member tables travel in the kernel arguments and are baked in).

@@ -56,6 +56,31 @@ def test_two_calls_in_a_row_match_the_allocating_entry_point():
         plan.destroy()
 
 
+def test_replays_from_a_hip_graph():
+    """The callers this entry point is for include code under HIP graph capture: the call is captured
+    once and replayed three times, with eager work and synchronisation between the replays and the
+    input changed in between; every replay must equal the allocating entry point run eagerly."""
+    plan, x_dev, dt, k = make_case(W=16, total=300_000, theta_dtype="f32", seed=23)
+    out = torch.zeros(k + 1, dtype=torch.float64, device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        nl.replica_spread_noalloc(plan, x_dev, dt, out)
+    torch.cuda.synchronize()
+    for replay in range(3):
+        x_dev.mul_(1.0 + 0.25 * replay)                              # eager work that changes the input
+        ref = torch.zeros(k + 1, dtype=torch.float64, device="cuda")
+        nl.replica_spread(plan, x_dev, dt, ref)
+        torch.cuda.synchronize()
+        out.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), replay
+        assert float(torch.randn(1 << 14, device="cuda").square().mean()) > 0.5   # more eager work
+    plan.destroy()
+
+
 def test_size_limit_and_argument_errors():
     x = torch.zeros((4, 64), device="cuda")
     out = torch.zeros(2, dtype=torch.float64, device="cuda")
