@@ -175,25 +175,32 @@ class LaunchPlan:
         self.worker_stride, self.W, self.theta_dtype = int(worker_stride), int(W), int(theta_dtype)
         self._segments = _segment_array(segments)
         self._num_segments = len(segments)
-        self._arena_key, self._arena_struct = None, None
-        self._hp_key, self._hp_struct = None, None
+        self._arenas, self._hps = {}, {}       # argument structs by value, never modified once built
         arena = self._arena(phi, delta, theta)
         _check(_lib.noloco_launch_plan_create(C.byref(arena), C.byref(self._handle)),
                "noloco_launch_plan_create")
 
     def _arena(self, phi, delta, theta):
+        """The noloco_arena struct for these base pointers. Structs are kept by pointer triple and
+        never changed after they are built, so threads sharing a plan cannot disturb each other."""
         key = (_ptr(phi), _ptr(delta), _ptr(theta))
-        if key != self._arena_key:          # the struct of the last base pointers is kept: no per-step rebuild
-            self._arena_struct = _Arena(*key, self.worker_stride, self.W, self.theta_dtype,
-                                        self._segments, self._num_segments)
-            self._arena_key = key
-        return self._arena_struct
+        arena = self._arenas.get(key)
+        if arena is None:
+            if len(self._arenas) >= 16:
+                self._arenas.clear()
+            arena = _Arena(*key, self.worker_stride, self.W, self.theta_dtype, self._segments, self._num_segments)
+            self._arenas[key] = arena
+        return arena
 
     def _hparams(self, hparams):
         key = (float(hparams[0]), float(hparams[1]), float(hparams[2]))
-        if key != self._hp_key:
-            self._hp_struct, self._hp_key = _HParams(*key), key
-        return self._hp_struct
+        hp = self._hps.get(key)
+        if hp is None:
+            if len(self._hps) >= 16:
+                self._hps.clear()
+            hp = _HParams(*key)
+            self._hps[key] = hp
+        return hp
 
     def info(self):
         e, r, t, te = C.c_int64(), C.c_int32(), C.c_int64(), C.c_int32()
