@@ -645,6 +645,9 @@ def main():
                 continue
             k = 12 if name.startswith("ragged") else 6     # the ragged schedule cycles n = 2, 4, 8
             extra.append(extra_outer(torch, nl, workloads, dev, name, args.placement, k, 3))
+        if args.placement == "spread":
+            # the same small arena from three neighbouring allocations, for comparison (see class Arena)
+            extra.append(extra_outer(torch, nl, workloads, dev, "gpt125m", "plain", 6, 3))
         m = measure_replica_spread(torch, nl, workloads, dev, workloads.make(DEFAULT_WORKLOAD), args.placement, 5, 2)
         extra.append({"op": "replica_spread", "workload": DEFAULT_WORKLOAD, "array": "phi (f32)", "steps": 5,
                       "resident_GB": m["resident_bytes"] / 1e9, "ms_per_step": sum(m["host_s"]) / 5 * 1e3,
